@@ -1,0 +1,167 @@
+/*
+ * laa — Local AdaAlter optimizer hot path for AMD MI355X (gfx950): C ABI.
+ *
+ * Method: arXiv 1911.09030, Algorithm 3 ("Local AdaAlter").  W workers are
+ * kept as a worker axis of replicas in one GPU's memory.  Each iteration every
+ * worker takes a local step
+ *     y   = x - eta * G / sqrt(B2_sync + t' * eps^2)        (Algorithm 3, update line)
+ *     B2 += G o G                                            (same line, accumulator)
+ * where B2_sync is the accumulator as it stood at the last synchronisation
+ * (identical on all workers; Section 4.2, "Lazy update of the denominators")
+ * and t' counts local steps since then.  Every H-th iteration x and B2 are
+ * replaced by their means over the worker axis (Algorithm 3, Synchronize).
+ *
+ * Conventions for every call
+ *   - Return value: LAA_OK (0) or a negative LAA_E* code; nothing throws.
+ *     laa_last_error() gives a message for the calling thread's last failure.
+ *   - "device" pointers are HIP device memory owned by the CALLER (allocated
+ *     e.g. through PyTorch).  The library allocates only small bookkeeping
+ *     buffers of its own (sparse dirty-row bitmap/list), freed by laa_destroy.
+ *   - All kernels are enqueued on the stream given to laa_attach and return
+ *     without waiting, except the getters that copy to host memory, which
+ *     synchronise that stream.
+ *   - Layout: x and acc are [W][d] row-major fp32 (worker-major, coordinate
+ *     contiguous); snap, a, xstar are [d] fp32.  64-bit indexing throughout.
+ *     Rows must be 4-byte aligned; the vectorised kernels are used when all
+ *     base pointers are 16-byte aligned and d % 4 == 0, a scalar path otherwise.
+ *   - A handle is not thread-safe; use one handle from one thread at a time.
+ */
+#ifndef LAA_H
+#define LAA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct laa_ctx *laa_handle;
+
+enum {
+    LAA_OK = 0,
+    LAA_EINVAL = -1,       /* bad argument (non-positive size, null pointer, ...) */
+    LAA_ENOTATTACHED = -2, /* state buffers not attached yet                       */
+    LAA_ESYNCDUE = -3,     /* H local steps taken since the last sync: call laa_sync */
+    LAA_EALIGN = -4,       /* pointer not 4-byte aligned                            */
+    LAA_EMODE = -5,        /* generator step without a generator, or bad mode       */
+    LAA_EHIP = -6,         /* a HIP runtime call failed                             */
+    LAA_ENODEVICE = -7     /* no usable GPU                                         */
+};
+
+/* Synthetic-gradient modes (a stand-in for the stochastic gradient of Algorithm 3,
+ * evaluated at each worker's own iterate; see laa_set_generator). */
+enum { LAA_GEN_QUADRATIC = 1, LAA_GEN_NOISE = 2 };
+/* Where the per-worker shift of the optimum comes from in LAA_GEN_QUADRATIC. */
+enum { LAA_OFF_NONE = 0, LAA_OFF_ARRAY = 1, LAA_OFF_PHILOX = 2 };
+/* Update rules: Algorithm 3 (default), and the paper's two comparison methods. */
+enum { LAA_ALGO_LOCAL_ADAALTER = 0, LAA_ALGO_DIST_ADAGRAD = 1, LAA_ALGO_LOCAL_SGD = 2 };
+
+const char *laa_last_error(void);
+
+/* Create a handle for d coordinates, W workers, sync period H, step size eta and
+ * the eps of Algorithm 3 (the kernels use eps^2, rounded once to fp32).  The
+ * initial accumulator b0 defaults to 1 (the paper's experiments; the theorem
+ * needs b0 >= 1).  Needs no GPU.  Errors: LAA_EINVAL for d<=0, W<=0, H<=0,
+ * eps<0, non-finite eta, null out. */
+int laa_create(int64_t d, int32_t W, int32_t H, double eta, double eps, laa_handle *out);
+
+/* Release the handle and the library's own bookkeeping buffers (never the
+ * caller's arrays).  Null is accepted. */
+int laa_destroy(laa_handle h);
+
+/* b0 of Algorithm 3's Initialize line; only before the first step. b0 >= 0. */
+int laa_set_b0(laa_handle h, double b0);
+
+/* Section 6.2 warm-up: eta_t = eta * min(1, t / warmup_steps) for the 1-based
+ * iteration t; 0 switches it off (constant eta, as in Algorithm 3). */
+int laa_set_warmup(laa_handle h, int64_t warmup_steps);
+
+/* Choose the update rule.  LAA_ALGO_DIST_ADAGRAD is Algorithm 1 (mean gradient,
+ * freshly updated accumulator under the root; use b0 = 0 for the paper's
+ * B2_0 = 0) and LAA_ALGO_LOCAL_SGD is Algorithm 2; both run through
+ * laa_step_dense / laa_step_gen only.  Only before the first step. */
+int laa_set_algorithm(laa_handle h, int32_t algo);
+
+/* Hand over the state arrays (device, caller-owned, must outlive the handle's
+ * use): x [W][d], acc [W][d] (running B2 of each worker), snap [d] (B2 at the
+ * last sync), and the HIP stream (hipStream_t, may be null for the default
+ * stream) on which all work is enqueued. */
+int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream);
+
+/* Algorithm 3, Initialize: x[w] = x0 for every w (x0 device [d], or null for
+ * zero), acc = snap = b0^2, counters reset, dirty rows cleared. */
+int laa_init_state(laa_handle h, const float *x0);
+
+/* One local step of every worker with explicit gradients grads [W][d] (device),
+ * already evaluated at the workers' current x.  LAA_ESYNCDUE after H steps
+ * without laa_sync. */
+int laa_local_step_dense(laa_handle h, const float *grads);
+
+/* Configure the fused synthetic gradient.  a, xstar [d] and off [W][d] are
+ * device arrays owned by the caller and read on every generator step.
+ *   LAA_GEN_QUADRATIC: g = a_j (x_wj - (xstar_j + off_wj)) + noise_scale * n_wjt
+ *   LAA_GEN_NOISE    : g = a_j * n_wjt            (xstar, off unused, may be null)
+ * n_wjt ~ N(0,1) from Philox4x32-10: counter (j/4, w, t, 3), key = seed, the four
+ * words mapped to u = ((r>>9)+0.5) 2^-23 and Box-Muller pairs (u0,u1),(u2,u3)
+ * giving the normals of coordinates 4(j/4)..4(j/4)+3.  off_mode LAA_OFF_PHILOX
+ * regenerates off_wj = off_scale * normal from counter (j/4, w, 0, 2) instead
+ * of reading an array; LAA_OFF_ARRAY reads off; LAA_OFF_NONE uses zero. */
+int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a, const float *xstar,
+                      const float *off, int32_t off_mode, float noise_scale, float off_scale);
+
+/* One local step with the gradient generated in the kernel at iteration t+1. */
+int laa_local_step_gen(laa_handle h);
+
+/* Write the gradient the next generator step would use into out [W][d] (device),
+ * without stepping.  For tests and for pre-computing gradient pools. */
+int laa_generate_gradient(laa_handle h, float *out);
+
+/* One local step with row-sparse gradients: the table is d / row_len rows of
+ * row_len floats; worker w updates rows idx[w][0..k) (device int32, [W][k])
+ * with values vals [W][k][row_len] (device).  Rows listed by one worker in one
+ * call must be distinct (different workers may list the same row).  Rows that
+ * are not listed are left untouched, which is exactly Algorithm 3 with a zero
+ * gradient there.  Indices outside [0, d/row_len) are skipped and counted
+ * (laa_get_counters bad_indices).  row_len must be a multiple of 4. */
+int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len);
+
+/* Algorithm 3, Synchronize: x[w] and acc[w] become the means over w, snap the
+ * mean acc.  After only sparse steps just the rows touched since the last sync
+ * are averaged (all other rows are already equal on every worker).  A call with
+ * no step since the last sync is a no-op; an early call (fewer than H steps) is
+ * allowed and restarts t' at 1. */
+int laa_sync(laa_handle h);
+
+/* One whole iteration of Algorithm 3: the local step and, when it is the H-th
+ * since the last sync, the averaging, fused into one pass over the state. */
+int laa_step_dense(laa_handle h, const float *grads);
+int laa_step_gen(laa_handle h);
+int laa_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len);
+
+/* Host-side counters: iterations done, local steps since the last sync, and the
+ * number of out-of-range sparse indices skipped so far (this one synchronises
+ * the stream).  Any pointer may be null. */
+int laa_get_counters(laa_handle h, int64_t *t, int32_t *steps_since_sync, int64_t *bad_indices);
+
+/* Rows touched by sparse steps since the last sync, ascending, into out (HOST,
+ * capacity cap); *n receives the total count even if it exceeds cap.
+ * Synchronises the stream. */
+int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n);
+
+/* Bytes the method itself had to move for everything enqueued so far
+ * (x, acc read+write per element-update, snap and generator arrays once per
+ * column-step, literal sync traffic), for bandwidth accounting. */
+int laa_bytes_moved(laa_handle h, uint64_t *algorithmic_bytes);
+
+/* Test hook: four raw Philox4x32-10 words for one counter/key, computed on the
+ * device, copied to out (HOST, 4 words). */
+int laa_debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t *out);
+
+/* A plain device-to-device copy kernel of n floats on the given stream; used to
+ * calibrate profiler byte counters against a known volume. */
+int laa_debug_copy(float *dst, const float *src, int64_t n, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAA_H */
