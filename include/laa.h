@@ -82,6 +82,11 @@ int laa_set_warmup(laa_handle h, int64_t warmup_steps);
  * laa_step_dense / laa_step_gen only.  Only before the first step. */
 int laa_set_algorithm(laa_handle h, int32_t algo);
 
+/* Tuning knob: how many workers' rows a thread loads before it starts computing (1, 2, 4 or 8,
+ * must divide W; default: the largest of those that divides W).  Results do not depend on it
+ * except through the order of the worker-axis sum when W exceeds it. */
+int laa_set_tile(laa_handle h, int32_t workers_per_batch);
+
 /* Hand over the state arrays (device, caller-owned, must outlive the handle's
  * use): x [W][d], acc [W][d] (running B2 of each worker), snap [d] (B2 at the
  * last sync), and the HIP stream (hipStream_t, may be null for the default

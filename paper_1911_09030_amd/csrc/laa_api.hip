@@ -1,0 +1,446 @@
+// C-ABI layer of the Local AdaAlter library: handle, argument checks, the step counter t' of
+// Algorithm 3 (arXiv 1911.09030) and kernel dispatch.  No arithmetic of the method lives here
+// except the scalars handed to the kernels (eta_t, t' eps^2).
+#include "../../include/laa.h"
+#include "laa_kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+struct laa_ctx {
+    int64_t d = 0;
+    int32_t W = 0, H = 0;
+    double eta = 0, eps = 0, b0 = 1.0;
+    int64_t warmup_steps = 0;
+    int32_t algo = LAA_ALGO_LOCAL_ADAALTER;
+    float *x = nullptr, *acc = nullptr, *snap = nullptr;
+    hipStream_t stream = nullptr;
+    bool attached = false, vec4 = false, gen_aligned16 = true;
+    int32_t wt = 1;
+    int64_t t = 0;          // iterations done
+    int32_t s = 0;          // local steps since the last sync (t' - 1 before a step)
+    // generator
+    int32_t gen_mode = 0, off_mode = 0;
+    uint64_t seed = 0;
+    const float *a = nullptr, *xstar = nullptr, *off = nullptr;
+    float noise_scale = 0, off_scale = 0;
+    // sparse bookkeeping (library-owned device memory)
+    int64_t n_rows = 0;
+    int32_t row_len = 0;
+    uint32_t *dirty = nullptr;
+    int32_t *dirty_list = nullptr;
+    uint32_t *dirty_count = nullptr, *scan_scratch = nullptr;
+    unsigned long long *bad = nullptr;
+    bool sparse_only_since_sync = true;   // every step since the last sync was a sparse one
+    uint64_t bytes = 0;
+};
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(LAA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+int pick_wt(int32_t W) { return W % 8 == 0 ? 8 : W % 4 == 0 ? 4 : W % 2 == 0 ? 2 : 1; }
+
+// eta_t = eta min(1, t / warmup_steps): Section 6.2, warm-up learning rates
+float eta_at(const laa_ctx *h, int64_t t)
+{
+    if (h->warmup_steps <= 0) return (float)h->eta;
+    const double r = (double)t / (double)h->warmup_steps;
+    return (float)(h->eta * (r < 1.0 ? r : 1.0));
+}
+
+int check_ready(laa_handle h)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (!h->attached) return fail(LAA_ENOTATTACHED, "state buffers not attached (laa_attach)");
+    return LAA_OK;
+}
+
+void free_sparse(laa_ctx *h)
+{
+    if (h->dirty) (void)hipFree(h->dirty);
+    if (h->dirty_list) (void)hipFree(h->dirty_list);
+    if (h->dirty_count) (void)hipFree(h->dirty_count);
+    if (h->scan_scratch) (void)hipFree(h->scan_scratch);
+    if (h->bad) (void)hipFree(h->bad);
+    h->dirty = nullptr; h->dirty_list = nullptr; h->dirty_count = nullptr; h->scan_scratch = nullptr; h->bad = nullptr;
+    h->n_rows = 0; h->row_len = 0;
+}
+
+int64_t n_dirty_words(int64_t n_rows) { return (n_rows + 31) / 32; }
+
+int ensure_sparse(laa_ctx *h, int32_t row_len)
+{
+    if (h->dirty && h->row_len == row_len) return LAA_OK;
+    if (h->dirty && h->s != 0)
+        return fail(LAA_EINVAL, "row_len changed between syncs (%d -> %d)", h->row_len, row_len);
+    free_sparse(h);
+    const int64_t n_rows = h->d / row_len;
+    if (n_rows > 0x7fffffffLL) return fail(LAA_EINVAL, "more than 2^31-1 rows");
+    const int64_t nw = n_dirty_words(n_rows);
+    const int64_t nblk = (nw + 1023) / 1024;
+    hipError_t e;
+    if ((e = hipMalloc(&h->dirty, nw * sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty bitmap");
+    if ((e = hipMalloc(&h->dirty_list, n_rows * sizeof(int32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty list");
+    if ((e = hipMalloc(&h->dirty_count, sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty count");
+    if ((e = hipMalloc(&h->scan_scratch, (nblk + 1) * sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc scan scratch");
+    if ((e = hipMalloc(&h->bad, sizeof(unsigned long long))) != hipSuccess) return hip_fail(e, "hipMalloc bad-index counter");
+    h->n_rows = n_rows;
+    h->row_len = row_len;
+    if ((e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream)) != hipSuccess) return hip_fail(e, "clear dirty bitmap");
+    if ((e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 2, h->stream)) != hipSuccess)
+        return hip_fail(e, "clear bad-index counter");
+    return LAA_OK;
+}
+
+int clear_dirty(laa_ctx *h)
+{
+    if (!h->dirty) return LAA_OK;
+    hipError_t e = laa::launch_fill_u32(h->dirty, 0u, n_dirty_words(h->n_rows), h->stream);
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "clear dirty bitmap");
+}
+
+enum StepKind { STEP_DENSE, STEP_GEN };
+
+// One local iteration (and, if fuse_sync, the averaging in the same pass).
+int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused_sync)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (kind == STEP_DENSE) {
+        if (!grads) return fail(LAA_EINVAL, "null gradient pointer");
+        if (!aligned(grads, 4)) return fail(LAA_EALIGN, "gradient pointer not 4-byte aligned");
+    } else if (h->gen_mode == 0) {
+        return fail(LAA_EMODE, "no gradient generator configured (laa_set_generator)");
+    }
+    const bool adagrad = h->algo == LAA_ALGO_DIST_ADAGRAD;
+    if (h->algo != LAA_ALGO_LOCAL_ADAALTER && !allow_fused_sync)
+        return fail(LAA_EMODE, "this update rule runs through laa_step_* only");
+    if (!adagrad && h->s >= h->H)
+        return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
+
+    laa::StepArgs a{};
+    a.x = h->x; a.acc = h->acc; a.snap = h->snap;
+    a.grads = kind == STEP_DENSE ? grads : nullptr;
+    a.a = h->a; a.xstar = h->xstar; a.off = h->off;
+    a.grad_out = nullptr;
+    a.d = h->d; a.W = h->W;
+    a.eta = eta_at(h, h->t + 1);
+    const float eps2 = (float)(h->eps * h->eps);
+    a.eps2 = eps2;
+    a.pad = (float)(h->s + 1) * eps2;                      // t' eps^2, t' = steps since sync + 1
+    a.noise_scale = h->noise_scale; a.off_scale = h->off_scale;
+    a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.t_lo = (uint32_t)(h->t + 1);
+    a.grad_source = kind == STEP_DENSE ? laa::GRAD_EXPLICIT : h->gen_mode;
+    a.off_source = kind == STEP_DENSE ? laa::OFFSET_NONE : h->off_mode;
+    a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
+    a.algo = h->algo;
+    a.wt = h->wt;
+    a.vec4 = h->vec4 && (kind == STEP_DENSE ? aligned(grads, 16) : h->gen_aligned16);
+    if (!a.vec4) a.wt = 1;
+
+    hipError_t e = laa::launch_step(a, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "step kernel launch");
+
+    const uint64_t W = (uint64_t)h->W, d = (uint64_t)h->d;
+    uint64_t col_bytes = 16 * W + 4;                        // x, acc read+write; snap read
+    if (kind == STEP_DENSE) col_bytes += 4 * W;
+    else col_bytes += (h->gen_mode == LAA_GEN_QUADRATIC ? 8 : 4) + (h->off_mode == LAA_OFF_ARRAY ? 4 * W : 0);
+    h->bytes += col_bytes * d;
+    h->t += 1;
+    h->s += 1;
+    h->sparse_only_since_sync = false;
+    if (a.sync) {
+        h->bytes += (16 * W + 4) * d;                       // literal sync traffic: read 2W, write 2W+1 floats
+        h->s = 0;
+        h->sparse_only_since_sync = true;
+        rc = clear_dirty(h);
+    }
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *laa_last_error(void) { return g_err; }
+
+int laa_create(int64_t d, int32_t W, int32_t H, double eta, double eps, laa_handle *out)
+{
+    if (!out) return fail(LAA_EINVAL, "null out pointer");
+    *out = nullptr;
+    if (d <= 0) return fail(LAA_EINVAL, "d must be positive (got %lld)", (long long)d);
+    if (W <= 0) return fail(LAA_EINVAL, "W must be positive (got %d)", W);
+    if (H <= 0) return fail(LAA_EINVAL, "H must be positive (got %d)", H);
+    if (!std::isfinite(eta)) return fail(LAA_EINVAL, "eta must be finite");
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return fail(LAA_EINVAL, "eps must be finite and >= 0");
+    if ((double)d * (double)W > 9.0e18) return fail(LAA_EINVAL, "W*d overflows");
+    laa_ctx *h = new (std::nothrow) laa_ctx();
+    if (!h) return fail(LAA_EINVAL, "out of host memory");
+    h->d = d; h->W = W; h->H = H; h->eta = eta; h->eps = eps;
+    h->wt = pick_wt(W);
+    *out = h;
+    return LAA_OK;
+}
+
+int laa_destroy(laa_handle h)
+{
+    if (!h) return LAA_OK;
+    free_sparse(h);
+    delete h;
+    return LAA_OK;
+}
+
+int laa_set_b0(laa_handle h, double b0)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (!(b0 >= 0.0) || !std::isfinite(b0)) return fail(LAA_EINVAL, "b0 must be finite and >= 0");
+    if (h->t != 0) return fail(LAA_EINVAL, "b0 can only be set before the first step");
+    h->b0 = b0;
+    return LAA_OK;
+}
+
+int laa_set_warmup(laa_handle h, int64_t warmup_steps)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (warmup_steps < 0) return fail(LAA_EINVAL, "warmup_steps must be >= 0");
+    h->warmup_steps = warmup_steps;
+    return LAA_OK;
+}
+
+int laa_set_algorithm(laa_handle h, int32_t algo)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (algo < LAA_ALGO_LOCAL_ADAALTER || algo > LAA_ALGO_LOCAL_SGD) return fail(LAA_EINVAL, "unknown update rule %d", algo);
+    if (h->t != 0) return fail(LAA_EINVAL, "the update rule can only be chosen before the first step");
+    h->algo = algo;
+    return LAA_OK;
+}
+
+int laa_set_tile(laa_handle h, int32_t workers_per_batch)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    const int32_t wt = workers_per_batch;
+    if (!(wt == 1 || wt == 2 || wt == 4 || wt == 8) || h->W % wt != 0)
+        return fail(LAA_EINVAL, "workers_per_batch must be 1, 2, 4 or 8 and divide W");
+    h->wt = wt;
+    return LAA_OK;
+}
+
+int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (!x || !acc || !snap) return fail(LAA_EINVAL, "null state pointer");
+    if (!aligned(x, 4) || !aligned(acc, 4) || !aligned(snap, 4)) return fail(LAA_EALIGN, "state pointer not 4-byte aligned");
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) return fail(LAA_ENODEVICE, "no HIP device available");
+    h->x = x; h->acc = acc; h->snap = snap;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    h->vec4 = h->d % 4 == 0 && aligned(x, 16) && aligned(acc, 16) && aligned(snap, 16);
+    h->attached = true;
+    return LAA_OK;
+}
+
+int laa_init_state(laa_handle h, const float *x0)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    const float b0sq = (float)(h->b0 * h->b0);
+    hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->W, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "init kernel launch");
+    h->t = 0; h->s = 0; h->bytes = 0; h->sparse_only_since_sync = true;
+    return clear_dirty(h);
+}
+
+int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a, const float *xstar,
+                      const float *off, int32_t off_mode, float noise_scale, float off_scale)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (mode != LAA_GEN_QUADRATIC && mode != LAA_GEN_NOISE) return fail(LAA_EMODE, "unknown generator mode %d", mode);
+    if (!a) return fail(LAA_EINVAL, "null a");
+    if (mode == LAA_GEN_QUADRATIC && !xstar) return fail(LAA_EINVAL, "null xstar");
+    if (mode == LAA_GEN_NOISE) off_mode = LAA_OFF_NONE;
+    if (off_mode < LAA_OFF_NONE || off_mode > LAA_OFF_PHILOX) return fail(LAA_EMODE, "unknown offset mode %d", off_mode);
+    if (off_mode == LAA_OFF_ARRAY && !off) return fail(LAA_EINVAL, "null off with LAA_OFF_ARRAY");
+    const bool a16 = aligned(a, 16) && (!xstar || aligned(xstar, 16)) && (off_mode != LAA_OFF_ARRAY || aligned(off, 16));
+    if (!aligned(a, 4) || (xstar && !aligned(xstar, 4)) || (off && !aligned(off, 4)))
+        return fail(LAA_EALIGN, "generator array not 4-byte aligned");
+    h->gen_aligned16 = a16;                                // else generator steps take the scalar path
+    h->gen_mode = mode; h->off_mode = off_mode; h->seed = seed;
+    h->a = a; h->xstar = xstar; h->off = off;
+    h->noise_scale = noise_scale; h->off_scale = off_scale;
+    return LAA_OK;
+}
+
+int laa_local_step_dense(laa_handle h, const float *grads) { return dense_step(h, STEP_DENSE, grads, false); }
+int laa_local_step_gen(laa_handle h) { return dense_step(h, STEP_GEN, nullptr, false); }
+int laa_step_dense(laa_handle h, const float *grads) { return dense_step(h, STEP_DENSE, grads, true); }
+int laa_step_gen(laa_handle h) { return dense_step(h, STEP_GEN, nullptr, true); }
+
+int laa_generate_gradient(laa_handle h, float *out)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (h->gen_mode == 0) return fail(LAA_EMODE, "no gradient generator configured (laa_set_generator)");
+    if (!out) return fail(LAA_EINVAL, "null out");
+    if (!aligned(out, 4)) return fail(LAA_EALIGN, "out not 4-byte aligned");
+    laa::StepArgs a{};
+    a.x = h->x; a.acc = h->acc; a.snap = h->snap;
+    a.a = h->a; a.xstar = h->xstar; a.off = h->off;
+    a.grad_out = out;
+    a.d = h->d; a.W = h->W;
+    a.noise_scale = h->noise_scale; a.off_scale = h->off_scale;
+    a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.t_lo = (uint32_t)(h->t + 1);
+    a.grad_source = h->gen_mode; a.off_source = h->off_mode;
+    a.vec4 = h->vec4 && h->gen_aligned16 && aligned(out, 16);
+    a.wt = a.vec4 ? h->wt : 1;
+    hipError_t e = laa::launch_step(a, h->stream);
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "gradient kernel launch");
+}
+
+int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (h->algo != LAA_ALGO_LOCAL_ADAALTER) return fail(LAA_EMODE, "sparse steps exist for Local AdaAlter only");
+    if (k < 0) return fail(LAA_EINVAL, "k must be >= 0");
+    if (row_len <= 0 || row_len % 4 != 0) return fail(LAA_EINVAL, "row_len must be a positive multiple of 4");
+    if (h->d % row_len != 0) return fail(LAA_EINVAL, "d is not a multiple of row_len");
+    if (k > 0 && (!idx || !vals)) return fail(LAA_EINVAL, "null idx/vals");
+    if (!aligned(h->x, 16) || !aligned(h->acc, 16) || !aligned(h->snap, 16) || (k > 0 && !aligned(vals, 16)))
+        return fail(LAA_EALIGN, "sparse path needs 16-byte aligned x, acc, snap, vals");
+    if (k > 0 && !aligned(idx, 4)) return fail(LAA_EALIGN, "idx not 4-byte aligned");
+    if (h->s >= h->H)
+        return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
+    rc = ensure_sparse(h, row_len);
+    if (rc != LAA_OK) return rc;
+    laa::SparseArgs a{};
+    a.x = h->x; a.acc = h->acc; a.snap = h->snap;
+    a.idx = idx; a.vals = vals; a.dirty = h->dirty; a.bad = h->bad;
+    a.d = h->d; a.n_rows = h->n_rows; a.W = h->W; a.k = k; a.row_len = row_len;
+    a.eta = eta_at(h, h->t + 1);
+    a.pad = (float)(h->s + 1) * (float)(h->eps * h->eps);
+    hipError_t e = laa::launch_sparse_step(a, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "sparse step kernel launch");
+    h->bytes += (uint64_t)h->W * (uint64_t)k * ((uint64_t)row_len * 24 + 4);
+    h->t += 1;
+    h->s += 1;
+    return LAA_OK;
+}
+
+int laa_sync(laa_handle h)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (h->algo == LAA_ALGO_DIST_ADAGRAD) return LAA_OK;     // every iteration is already synchronous
+    if (h->s == 0) return LAA_OK;
+    hipError_t e;
+    const bool x_only = h->algo == LAA_ALGO_LOCAL_SGD;
+    if (h->dirty && h->sparse_only_since_sync && !x_only) {
+        e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
+        if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->d, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
+        if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
+    } else {
+        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->stream);
+        if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
+        h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
+    }
+    h->s = 0;
+    h->sparse_only_since_sync = true;
+    return clear_dirty(h);
+}
+
+int laa_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len)
+{
+    int rc = laa_local_step_sparse(h, idx, vals, k, row_len);
+    if (rc == LAA_OK && h->s == h->H) rc = laa_sync(h);
+    return rc;
+}
+
+int laa_get_counters(laa_handle h, int64_t *t, int32_t *steps_since_sync, int64_t *bad_indices)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (t) *t = h->t;
+    if (steps_since_sync) *steps_since_sync = h->s;
+    if (bad_indices) {
+        *bad_indices = 0;
+        if (h->bad) {
+            unsigned long long v = 0;
+            hipError_t e = hipMemcpyAsync(&v, h->bad, sizeof(v), hipMemcpyDeviceToHost, h->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+            if (e != hipSuccess) return hip_fail(e, "reading the bad-index counter");
+            *bad_indices = (int64_t)v;
+        }
+    }
+    return LAA_OK;
+}
+
+int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (!n) return fail(LAA_EINVAL, "null n");
+    if (cap < 0 || (cap > 0 && !out)) return fail(LAA_EINVAL, "bad out/cap");
+    *n = 0;
+    if (!h->dirty) return LAA_OK;
+    hipError_t e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
+    uint32_t cnt = 0;
+    e = hipMemcpyAsync(&cnt, h->dirty_count, sizeof(cnt), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(e, "reading the dirty-row count");
+    *n = cnt;
+    const int64_t m = cnt < cap ? cnt : cap;
+    if (m > 0) {
+        e = hipMemcpyAsync(out, h->dirty_list, m * sizeof(int32_t), hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) return hip_fail(e, "copying the dirty-row list");
+    }
+    return LAA_OK;
+}
+
+int laa_bytes_moved(laa_handle h, uint64_t *algorithmic_bytes)
+{
+    if (!h || !algorithmic_bytes) return fail(LAA_EINVAL, "null argument");
+    *algorithmic_bytes = h->bytes;
+    return LAA_OK;
+}
+
+int laa_debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t *out)
+{
+    if (!ctr || !key || !out) return fail(LAA_EINVAL, "null argument");
+    hipError_t e = laa::debug_philox(ctr, key, out);
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "philox debug kernel");
+}
+
+int laa_debug_copy(float *dst, const float *src, int64_t n, void *hip_stream)
+{
+    if (!dst || !src || n <= 0 || n % 4 != 0 || !aligned(dst, 16) || !aligned(src, 16))
+        return fail(LAA_EINVAL, "copy needs 16-byte aligned pointers and n a positive multiple of 4");
+    hipError_t e = laa::launch_copy(dst, src, n, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "copy kernel launch");
+}
+
+}  // extern "C"

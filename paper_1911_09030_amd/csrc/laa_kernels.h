@@ -1,0 +1,64 @@
+// Internal launcher interface between the C-ABI layer (laa_api.hip) and the
+// gfx950 kernels (laa_kernels.hip).  Plain device pointers and sizes only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace laa {
+
+enum GradSource { GRAD_EXPLICIT = 0, GRAD_QUADRATIC = 1, GRAD_NOISE = 2 };
+enum OffsetSource { OFFSET_NONE = 0, OFFSET_ARRAY = 1, OFFSET_PHILOX = 2 };
+enum Algo { ALGO_LOCAL_ADAALTER = 0, ALGO_DIST_ADAGRAD = 1, ALGO_LOCAL_SGD = 2 };
+
+struct StepArgs {
+    float *x;            // [W][d]
+    float *acc;          // [W][d]
+    float *snap;         // [d]
+    const float *grads;  // [W][d] explicit gradients, or null
+    const float *a;      // [d]
+    const float *xstar;  // [d]
+    const float *off;    // [W][d]
+    float *grad_out;     // [W][d]: write the generated gradient here instead of stepping
+    int64_t d;
+    int32_t W;
+    float eta;           // eta_t of this iteration
+    float pad;           // t' * eps^2
+    float eps2;
+    float noise_scale, off_scale;
+    uint32_t seed_lo, seed_hi;
+    uint32_t t_lo;       // iteration number of this step (low 32 bits), Philox counter word
+    int32_t grad_source, off_source;
+    bool sync;           // average over the worker axis in the same pass
+    bool vec4;           // pointers 16-byte aligned and d % 4 == 0
+    int32_t wt;          // workers loaded per batch (1, 2, 4 or 8; must divide W)
+    int32_t algo;
+};
+
+hipError_t launch_step(const StepArgs &a, hipStream_t s);
+hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int32_t W, bool vec4, int32_t wt, bool x_only,
+                       hipStream_t s);
+hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int32_t W,
+                       hipStream_t s);
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
+
+struct SparseArgs {
+    float *x, *acc, *snap;
+    const int32_t *idx;  // [W][k]
+    const float *vals;   // [W][k][row_len]
+    uint32_t *dirty;     // bitmap, one bit per row
+    unsigned long long *bad; // count of skipped out-of-range indices
+    int64_t d;
+    int64_t n_rows;
+    int32_t W, k, row_len;
+    float eta, pad;
+};
+hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s);
+// bitmap -> ascending row list (device) + count (device); scratch holds one uint32 per 1024 bitmap words (+1)
+hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
+                                uint32_t *scratch, hipStream_t s);
+hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t d, int32_t W, int32_t row_len,
+                            const int32_t *list, const uint32_t *count, hipStream_t s);
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
+hipError_t debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+}  // namespace laa

@@ -1,0 +1,666 @@
+// Local AdaAlter (arXiv 1911.09030, Algorithm 3) kernels for gfx950 (MI355X, CDNA4).
+//
+// The path is elementwise and HBM-bound: no MFMA, no LDS for the dense kernels.
+// Layout: x, acc are [W][d] (worker-major); one thread owns a group of four
+// consecutive coordinates for ALL W workers, so
+//   * every global access is a 16-byte load/store, consecutive lanes touch
+//     consecutive 16-byte words (1 KiB per wavefront per instruction),
+//   * the quantities shared by the workers of a column (the lazily updated
+//     denominator of Section 4.2, the quadratic's a and xstar) are read and the
+//     square root / division are evaluated once per column, not once per worker,
+//   * the worker-axis mean of the Synchronize branch is a register reduction
+//     (a balanced tree over the W values the thread already holds); no
+//     cross-lane traffic is needed with this layout.
+// State is streamed once per step, so loads/stores of x, acc and gradients are
+// non-temporal.
+#include "laa_kernels.h"
+
+namespace laa {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+static constexpr int BLOCK = 256;
+
+// ------------------------------------------------------------------------------------------
+// small vector pack: VEC = 4 (16-byte accesses) or VEC = 1 (fallback for unaligned / d % 4 != 0)
+template <int VEC> struct Pack { float v[VEC]; };
+
+template <int VEC, bool NT> __device__ __forceinline__ Pack<VEC> ld(const float *p)
+{
+    Pack<VEC> r;
+    if constexpr (VEC == 4) {
+        v4f t = NT ? __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p)) : *reinterpret_cast<const v4f *>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = NT ? __builtin_nontemporal_load(p) : *p;
+    }
+    return r;
+}
+template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const Pack<VEC> &r)
+{
+    if constexpr (VEC == 4) {
+        v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]};
+        if (NT) __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(p));
+        else *reinterpret_cast<v4f *>(p) = t;
+    } else {
+        if (NT) __builtin_nontemporal_store(r.v[0], p);
+        else *p = r.v[0];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): per round hi0:lo0 = M0*c0, hi1:lo1 = M1*c2,
+// (c0,c1,c2,c3) <- (hi1^c1^k0, lo1, hi0^c3^k1, lo0); the key advances by the Weyl constants.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&r)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3;
+}
+
+// u = ((r >> 9) + 0.5) * 2^-23: 23 random bits, never 0 or 1, exact in fp32
+__device__ __forceinline__ float u01(uint32_t r) { return fmaf((float)(r >> 9), 0x1p-23f, 0x1p-24f); }
+
+// Four standard normals for the coordinates 4*qa .. 4*qa+3 of worker w at iteration word t on a stream.
+// Box-Muller on (u0,u1) and (u2,u3); the angle is taken in half-turns (2*u exact) so that no
+// rounding of 2*pi*u enters.
+__device__ __forceinline__ void normals4(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream, uint64_t qa, uint32_t w,
+                                         uint32_t t, float (&n)[4])
+{
+    uint32_t r[4];
+    philox4x32_10((uint32_t)qa, w, t, stream + (uint32_t)(qa >> 32) * 16u, seed_lo, seed_hi, r);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float u0 = u01(r[2 * p]), u1 = u01(r[2 * p + 1]);
+        const float rad = sqrtf(-2.0f * logf(u0));
+        float sn, cs;
+        sincospif(2.0f * u1, &sn, &cs);
+        n[2 * p] = rad * cs;
+        n[2 * p + 1] = rad * sn;
+    }
+}
+
+static constexpr uint32_t STREAM_OFFSET = 2, STREAM_NOISE = 3;
+
+// Gradient of worker w for the VEC coordinates starting at j, evaluated at xv (the worker's x before the step).
+//   quadratic: g = a (x - (xstar + off)) + noise_scale n        noise: g = a n
+template <int VEC, int GS, int OS>
+__device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int32_t w, const Pack<VEC> &xv,
+                                              const Pack<VEC> &av, const Pack<VEC> &xs)
+{
+    Pack<VEC> g;
+    const int64_t row = (int64_t)w * a.d + j;
+    if constexpr (GS == GRAD_EXPLICIT) {
+        g = ld<VEC, true>(a.grads + row);
+    } else {
+        const uint64_t qa = (uint64_t)j >> 2;
+        float n[4];
+        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, (uint32_t)w, a.t_lo, n);
+        if constexpr (GS == GRAD_NOISE) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) g.v[e] = av.v[e] * n[VEC == 4 ? e : (int)(j & 3)];
+        } else {
+            Pack<VEC> o;
+            if constexpr (OS == OFFSET_ARRAY) {
+                o = ld<VEC, true>(a.off + row);
+            } else if constexpr (OS == OFFSET_PHILOX) {
+                float m[4];
+                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, (uint32_t)w, 0u, m);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) o.v[e] = a.off_scale * m[VEC == 4 ? e : (int)(j & 3)];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) o.v[e] = 0.0f;
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float nz = n[VEC == 4 ? e : (int)(j & 3)];
+                g.v[e] = fmaf(av.v[e], xv.v[e] - (xs.v[e] + o.v[e]), a.noise_scale * nz);
+            }
+        }
+    }
+    return g;
+}
+
+// balanced tree over the WT packs of one batch; batches are added in ascending order
+template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const Pack<VEC> (&v)[WT])
+{
+    Pack<VEC> r;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        if constexpr (WT == 1) r.v[e] = v[0].v[e];
+        else if constexpr (WT == 2) r.v[e] = v[0].v[e] + v[1].v[e];
+        else if constexpr (WT == 4) r.v[e] = (v[0].v[e] + v[1].v[e]) + (v[2].v[e] + v[3].v[e]);
+        else r.v[e] = ((v[0].v[e] + v[1].v[e]) + (v[2].v[e] + v[3].v[e])) +
+                      ((v[4].v[e] + v[5].v[e]) + (v[6].v[e] + v[7].v[e]));
+    }
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------
+// One iteration of Algorithm 3 for every worker of a column group.
+//   den   = sqrt(B2_sync + t' eps^2)   (value of the accumulator at the last sync, shared by all workers)
+//   y     = x - eta g / den ;  A2 = B2 + g o g
+//   SYNC: x, B2 <- mean over workers of y, A2; B2_sync <- that mean      (Synchronize branch)
+//   GRAD_ONLY: write g and change nothing (used to materialise gradients)
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
+__global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs a)
+{
+    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (j >= a.d) return;
+
+    Pack<VEC> av, xs, step;
+    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
+    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
+    if constexpr (!GRAD_ONLY) {
+        const Pack<VEC> sn = ld<VEC, false>(a.snap + j);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) step.v[e] = a.eta / sqrtf(sn.v[e] + a.pad);
+    }
+
+    Pack<VEC> sx, sb;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sx.v[e] = sb.v[e] = 0.0f;
+
+    for (int32_t w0 = 0; w0 < a.W; w0 += WT) {
+        Pack<VEC> xv[WT], bv[WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i) {
+            const int64_t row = (int64_t)(w0 + i) * a.d + j;
+            if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, true>(a.x + row);
+            if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, true>(a.acc + row);
+        }
+#pragma unroll
+        for (int i = 0; i < WT; ++i) {
+            const int64_t row = (int64_t)(w0 + i) * a.d + j;
+            const Pack<VEC> g = gradient<VEC, GS, OS>(a, j, w0 + i, xv[i], av, xs);
+            if constexpr (GRAD_ONLY) {
+                st<VEC, true>(a.grad_out + row, g);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    xv[i].v[e] = fmaf(-g.v[e], step.v[e], xv[i].v[e]);
+                    bv[i].v[e] = fmaf(g.v[e], g.v[e], bv[i].v[e]);
+                }
+                if constexpr (!SYNC) {
+                    st<VEC, true>(a.x + row, xv[i]);
+                    st<VEC, true>(a.acc + row, bv[i]);
+                }
+            }
+        }
+        if constexpr (SYNC && !GRAD_ONLY) {
+            const Pack<VEC> tx = tree_sum<VEC, WT>(xv), tb = tree_sum<VEC, WT>(bv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { sx.v[e] += tx.v[e]; sb.v[e] += tb.v[e]; }
+        }
+    }
+    if constexpr (SYNC && !GRAD_ONLY) {
+        const float fw = (float)a.W;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
+        for (int32_t w = 0; w < a.W; ++w) {
+            const int64_t row = (int64_t)w * a.d + j;
+            st<VEC, true>(a.x + row, sx);
+            st<VEC, true>(a.acc + row, sb);
+        }
+        st<VEC, false>(a.snap + j, sb);
+    }
+}
+
+// Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
+// shared iterate kept in every worker's row.  Algorithm 2 (Local SGD): y = x - eta G per worker.
+template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
+__global__ __launch_bounds__(BLOCK) void baseline_kernel(const StepArgs a)
+{
+    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (j >= a.d) return;
+    Pack<VEC> av, xs;
+    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
+    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
+    Pack<VEC> sg, sx;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sg.v[e] = sx.v[e] = 0.0f;
+    Pack<VEC> x0;
+    for (int32_t w0 = 0; w0 < a.W; w0 += WT) {
+        Pack<VEC> xv[WT], gv[WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i) xv[i] = ld<VEC, true>(a.x + (int64_t)(w0 + i) * a.d + j);
+        if (w0 == 0) x0 = xv[0];
+#pragma unroll
+        for (int i = 0; i < WT; ++i) {
+            gv[i] = gradient<VEC, GS, OS>(a, j, w0 + i, xv[i], av, xs);
+            if constexpr (ALGO == ALGO_LOCAL_SGD) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) xv[i].v[e] = fmaf(-a.eta, gv[i].v[e], xv[i].v[e]);
+                if constexpr (!SYNC) st<VEC, true>(a.x + (int64_t)(w0 + i) * a.d + j, xv[i]);
+            }
+        }
+        if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
+            const Pack<VEC> t = tree_sum<VEC, WT>(gv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sg.v[e] += t.v[e];
+        } else if constexpr (SYNC) {
+            const Pack<VEC> t = tree_sum<VEC, WT>(xv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sx.v[e] += t.v[e];
+        }
+    }
+    const float fw = (float)a.W;
+    if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
+        Pack<VEC> b2 = ld<VEC, false>(a.snap + j);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float g = sg.v[e] / fw;
+            b2.v[e] = fmaf(g, g, b2.v[e]);
+            x0.v[e] = x0.v[e] - (a.eta * g) / sqrtf(b2.v[e] + a.eps2);
+        }
+        for (int32_t w = 0; w < a.W; ++w) {
+            st<VEC, true>(a.x + (int64_t)w * a.d + j, x0);
+            st<VEC, true>(a.acc + (int64_t)w * a.d + j, b2);
+        }
+        st<VEC, false>(a.snap + j, b2);
+    } else if constexpr (SYNC) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sx.v[e] = sx.v[e] / fw;
+        for (int32_t w = 0; w < a.W; ++w) st<VEC, true>(a.x + (int64_t)w * a.d + j, sx);
+    }
+}
+
+// Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
+template <int VEC, int WT, bool X_ONLY>
+__global__ __launch_bounds__(BLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                     float *__restrict__ snap, int64_t d, int32_t W)
+{
+    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
+    if (j >= d) return;
+    Pack<VEC> sx, sb;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sx.v[e] = sb.v[e] = 0.0f;
+    for (int32_t w0 = 0; w0 < W; w0 += WT) {
+        Pack<VEC> xv[WT], bv[WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i) {
+            xv[i] = ld<VEC, true>(x + (int64_t)(w0 + i) * d + j);
+            if constexpr (!X_ONLY) bv[i] = ld<VEC, true>(acc + (int64_t)(w0 + i) * d + j);
+        }
+        const Pack<VEC> tx = tree_sum<VEC, WT>(xv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sx.v[e] += tx.v[e];
+        if constexpr (!X_ONLY) {
+            const Pack<VEC> tb = tree_sum<VEC, WT>(bv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sb.v[e] += tb.v[e];
+        }
+    }
+    const float fw = (float)W;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
+    for (int32_t w = 0; w < W; ++w) {
+        st<VEC, true>(x + (int64_t)w * d + j, sx);
+        if constexpr (!X_ONLY) st<VEC, true>(acc + (int64_t)w * d + j, sb);
+    }
+    if constexpr (!X_ONLY) st<VEC, false>(snap + j, sb);
+}
+
+// Algorithm 3, Initialize: x[w] = x0 (or 0), acc = snap = b0^2.
+__global__ __launch_bounds__(BLOCK) void init_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                     float *__restrict__ snap, const float *__restrict__ x0,
+                                                     float b0sq, int64_t d, int32_t W)
+{
+    const int64_t j = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (j >= d) return;
+    const float v = x0 ? x0[j] : 0.0f;
+    for (int32_t w = 0; w < W; ++w) {
+        x[(int64_t)w * d + j] = v;
+        acc[(int64_t)w * d + j] = b0sq;
+    }
+    snap[j] = b0sq;
+}
+
+__global__ __launch_bounds__(BLOCK) void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ __launch_bounds__(BLOCK) void copy_kernel(v4f *__restrict__ dst, const v4f *__restrict__ src, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-sparse step: one wavefront per (worker, listed row).  Rows not listed are not touched: with a zero
+// gradient Algorithm 3 leaves y = x and A2 = B2.  The row's bit in the dirty bitmap is set so the next
+// sync averages only rows some worker changed.
+static constexpr int WAVE = 64;
+static constexpr int WAVES_PER_BLOCK = BLOCK / WAVE;
+
+__global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
+{
+    const int64_t pair = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x / WAVE);
+    const int lane = threadIdx.x % WAVE;
+    if (pair >= (int64_t)a.W * a.k) return;
+    const int32_t w = (int32_t)(pair / a.k);
+    const int32_t r = a.idx[pair];
+    if (r < 0 || (int64_t)r >= a.n_rows) {
+        if (lane == 0) atomicAdd(a.bad, 1ull);
+        return;
+    }
+    const float *gv = a.vals + pair * a.row_len;
+    const int64_t col = (int64_t)r * a.row_len;
+    float *xr = a.x + (int64_t)w * a.d + col;
+    float *br = a.acc + (int64_t)w * a.d + col;
+    const float *sr = a.snap + col;
+    for (int32_t e = lane * 4; e < a.row_len; e += WAVE * 4) {
+        const Pack<4> g = ld<4, true>(gv + e);
+        const Pack<4> s = ld<4, false>(sr + e);
+        Pack<4> xv = ld<4, false>(xr + e), bv = ld<4, false>(br + e);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float step = a.eta / sqrtf(s.v[c] + a.pad);
+            xv.v[c] = fmaf(-g.v[c], step, xv.v[c]);
+            bv.v[c] = fmaf(g.v[c], g.v[c], bv.v[c]);
+        }
+        st<4, false>(xr + e, xv);
+        st<4, false>(br + e, bv);
+    }
+    if (lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+}
+
+// Dirty bitmap -> ascending list of rows.  Three passes: per-block bit counts, scan of the block
+// counts by one block, then each block writes its rows at its offset.
+static constexpr int WORDS_PER_THREAD = 4;
+static constexpr int WORDS_PER_BLOCK = BLOCK * WORDS_PER_THREAD;
+
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *total)
+{
+    __shared__ uint32_t sh[BLOCK];
+    const int t = threadIdx.x;
+    sh[t] = v;
+    __syncthreads();
+    for (int o = 1; o < BLOCK; o <<= 1) {
+        const uint32_t add = t >= o ? sh[t - o] : 0u;
+        __syncthreads();
+        sh[t] += add;
+        __syncthreads();
+    }
+    const uint32_t incl = sh[t];
+    *total = sh[BLOCK - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(BLOCK) void dirty_count_kernel(const uint32_t *__restrict__ dirty, int64_t n_words,
+                                                            uint32_t *__restrict__ block_counts)
+{
+    const int64_t w0 = (int64_t)blockIdx.x * WORDS_PER_BLOCK + (int64_t)threadIdx.x * WORDS_PER_THREAD;
+    uint32_t c = 0;
+    for (int i = 0; i < WORDS_PER_THREAD; ++i)
+        if (w0 + i < n_words) c += __popc(dirty[w0 + i]);
+    uint32_t total;
+    block_exclusive_scan(c, &total);
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(BLOCK) void dirty_scan_kernel(uint32_t *__restrict__ block_counts, int32_t n_blocks,
+                                                           uint32_t *__restrict__ count)
+{
+    uint32_t running = 0;
+    for (int32_t base = 0; base < n_blocks; base += BLOCK) {
+        const int32_t i = base + threadIdx.x;
+        const uint32_t v = i < n_blocks ? block_counts[i] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan(v, &total);
+        if (i < n_blocks) block_counts[i] = running + ex;
+        running += total;
+    }
+    if (threadIdx.x == 0) *count = running;
+}
+
+__global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__restrict__ dirty, int64_t n_words,
+                                                            const uint32_t *__restrict__ block_offsets,
+                                                            int32_t *__restrict__ list)
+{
+    const int64_t w0 = (int64_t)blockIdx.x * WORDS_PER_BLOCK + (int64_t)threadIdx.x * WORDS_PER_THREAD;
+    uint32_t words[WORDS_PER_THREAD];
+    uint32_t c = 0;
+    for (int i = 0; i < WORDS_PER_THREAD; ++i) {
+        words[i] = w0 + i < n_words ? dirty[w0 + i] : 0u;
+        c += __popc(words[i]);
+    }
+    uint32_t total;
+    uint32_t pos = block_offsets[blockIdx.x] + block_exclusive_scan(c, &total);
+    for (int i = 0; i < WORDS_PER_THREAD; ++i) {
+        uint32_t m = words[i];
+        while (m) {
+            const int b = __ffs(m) - 1;
+            m &= m - 1;
+            list[pos++] = (int32_t)((w0 + i) * 32 + b);
+        }
+    }
+}
+
+// Synchronize branch restricted to the listed rows; a fixed grid of wavefronts strides over the list,
+// whose length is read from device memory.
+template <int WT>
+__global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                          float *__restrict__ snap, int64_t d, int32_t W,
+                                                          int32_t row_len, const int32_t *__restrict__ list,
+                                                          const uint32_t *__restrict__ count)
+{
+    const uint32_t n = *count;
+    const uint32_t n_waves = gridDim.x * WAVES_PER_BLOCK;
+    const int lane = threadIdx.x % WAVE;
+    const float fw = (float)W;
+    for (uint32_t i = blockIdx.x * WAVES_PER_BLOCK + threadIdx.x / WAVE; i < n; i += n_waves) {
+        const int64_t col = (int64_t)list[i] * row_len;
+        for (int32_t e = lane * 4; e < row_len; e += WAVE * 4) {
+            Pack<4> sx, sb;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sx.v[c] = sb.v[c] = 0.0f;
+            for (int32_t w0 = 0; w0 < W; w0 += WT) {
+                Pack<4> xv[WT], bv[WT];
+#pragma unroll
+                for (int k = 0; k < WT; ++k) {
+                    xv[k] = ld<4, false>(x + (int64_t)(w0 + k) * d + col + e);
+                    bv[k] = ld<4, false>(acc + (int64_t)(w0 + k) * d + col + e);
+                }
+                const Pack<4> tx = tree_sum<4, WT>(xv), tb = tree_sum<4, WT>(bv);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { sx.v[c] += tx.v[c]; sb.v[c] += tb.v[c]; }
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { sx.v[c] = sx.v[c] / fw; sb.v[c] = sb.v[c] / fw; }
+            for (int32_t w = 0; w < W; ++w) {
+                st<4, false>(x + (int64_t)w * d + col + e, sx);
+                st<4, false>(acc + (int64_t)w * d + col + e, sb);
+            }
+            st<4, false>(snap + col + e, sb);
+        }
+    }
+}
+
+__global__ void philox_debug_kernel(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                    uint32_t *out)
+{
+    uint32_t r[4];
+    philox4x32_10(c0, c1, c2, c3, k0, k1, r);
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        for (int i = 0; i < 4; ++i) out[i] = r[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+static inline bool grid_for(int64_t n_threads, dim3 *grid)
+{
+    const int64_t nb = (n_threads + BLOCK - 1) / BLOCK;
+    if (nb <= 0 || nb > 0x7fffffffLL) return false;
+    *grid = dim3((unsigned)nb);
+    return true;
+}
+
+template <int VEC, int WT, int GS, int OS>
+static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
+{
+    if (a.grad_out) {
+        if constexpr (GS == GRAD_EXPLICIT) return hipErrorInvalidValue;
+        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true>), grid, dim3(BLOCK), 0, s, a);
+    } else if (a.algo == ALGO_LOCAL_ADAALTER) {
+        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false>), grid, dim3(BLOCK), 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false>), grid, dim3(BLOCK), 0, s, a);
+    } else if (a.algo == ALGO_DIST_ADAGRAD) {
+        hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(BLOCK), 0, s, a);
+    } else {
+        if (a.sync)
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, true>), grid, dim3(BLOCK), 0, s, a);
+        else
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, false>), grid, dim3(BLOCK), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <int VEC, int WT> static hipError_t launch_step_2(const StepArgs &a, dim3 grid, hipStream_t s)
+{
+    switch (a.grad_source) {
+    case GRAD_EXPLICIT: return launch_step_4<VEC, WT, GRAD_EXPLICIT, OFFSET_NONE>(a, grid, s);
+    case GRAD_NOISE: return launch_step_4<VEC, WT, GRAD_NOISE, OFFSET_NONE>(a, grid, s);
+    case GRAD_QUADRATIC:
+        switch (a.off_source) {
+        case OFFSET_NONE: return launch_step_4<VEC, WT, GRAD_QUADRATIC, OFFSET_NONE>(a, grid, s);
+        case OFFSET_ARRAY: return launch_step_4<VEC, WT, GRAD_QUADRATIC, OFFSET_ARRAY>(a, grid, s);
+        case OFFSET_PHILOX: return launch_step_4<VEC, WT, GRAD_QUADRATIC, OFFSET_PHILOX>(a, grid, s);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_step(const StepArgs &a, hipStream_t s)
+{
+    if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0) return hipErrorInvalidValue;
+    dim3 grid;
+    if (a.vec4) {
+        if (a.d % 4 != 0 || !grid_for(a.d / 4, &grid)) return hipErrorInvalidValue;
+        switch (a.wt) {
+        case 1: return launch_step_2<4, 1>(a, grid, s);
+        case 2: return launch_step_2<4, 2>(a, grid, s);
+        case 4: return launch_step_2<4, 4>(a, grid, s);
+        case 8: return launch_step_2<4, 8>(a, grid, s);
+        }
+        return hipErrorInvalidValue;
+    }
+    if (!grid_for(a.d, &grid)) return hipErrorInvalidValue;
+    return launch_step_2<1, 1>(a, grid, s);
+}
+
+template <int VEC, int WT>
+static hipError_t launch_mean_2(float *x, float *acc, float *snap, int64_t d, int32_t W, bool x_only, dim3 grid,
+                                hipStream_t s)
+{
+    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(BLOCK), 0, s, x, acc, snap, d, W);
+    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(BLOCK), 0, s, x, acc, snap, d, W);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int32_t W, bool vec4, int32_t wt, bool x_only,
+                       hipStream_t s)
+{
+    if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0) return hipErrorInvalidValue;
+    dim3 grid;
+    if (vec4) {
+        if (d % 4 != 0 || !grid_for(d / 4, &grid)) return hipErrorInvalidValue;
+        switch (wt) {
+        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, W, x_only, grid, s);
+        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, W, x_only, grid, s);
+        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, W, x_only, grid, s);
+        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, W, x_only, grid, s);
+        }
+        return hipErrorInvalidValue;
+    }
+    if (!grid_for(d, &grid)) return hipErrorInvalidValue;
+    return launch_mean_2<1, 1>(x, acc, snap, d, W, x_only, grid, s);
+}
+
+hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int32_t W,
+                       hipStream_t s)
+{
+    dim3 grid;
+    if (!grid_for(d, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(init_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, x0, b0sq, d, W);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    dim3 grid;
+    if (!grid_for(n, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fill_u32_kernel, grid, dim3(BLOCK), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s)
+{
+    if (n <= 0 || n % 4 != 0) return hipErrorInvalidValue;
+    dim3 grid;
+    if (!grid_for(n / 4, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_kernel, grid, dim3(BLOCK), 0, s, reinterpret_cast<v4f *>(dst),
+                       reinterpret_cast<const v4f *>(src), n / 4);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s)
+{
+    const int64_t pairs = (int64_t)a.W * a.k;
+    if (pairs == 0) return hipSuccess;
+    if (a.row_len <= 0 || a.row_len % 4 != 0 || a.n_rows * a.row_len != a.d) return hipErrorInvalidValue;
+    const int64_t nb = (pairs + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sparse_step_kernel, dim3((unsigned)nb), dim3(BLOCK), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
+                                uint32_t *scratch, hipStream_t s)
+{
+    const int64_t n_words = (n_rows + 31) / 32;
+    const int64_t nb = (n_words + WORDS_PER_BLOCK - 1) / WORDS_PER_BLOCK;
+    if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dirty_count_kernel, dim3((unsigned)nb), dim3(BLOCK), 0, s, dirty, n_words, scratch);
+    hipLaunchKernelGGL(dirty_scan_kernel, dim3(1), dim3(BLOCK), 0, s, scratch, (int32_t)nb, count);
+    hipLaunchKernelGGL(dirty_write_kernel, dim3((unsigned)nb), dim3(BLOCK), 0, s, dirty, n_words, scratch, list);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t d, int32_t W, int32_t row_len,
+                            const int32_t *list, const uint32_t *count, hipStream_t s)
+{
+    const dim3 grid(2048), block(BLOCK);
+    if (W % 8 == 0) hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
+    else if (W % 4 == 0) hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
+    else if (W % 2 == 0) hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
+    else hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
+    return hipGetLastError();
+}
+
+hipError_t debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t *dev = nullptr;
+    hipError_t e = hipMalloc(&dev, 4 * sizeof(uint32_t));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(philox_debug_kernel, dim3(1), dim3(64), 0, 0, ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1], dev);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(out, dev, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    (void)hipFree(dev);
+    return e;
+}
+
+}  // namespace laa

@@ -1,0 +1,434 @@
+"""GPU parity tests: the HIP path, called through the C-ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Oracle
+from paper_1911_09030_amd import workloads as wl
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1911_09030_amd import binding
+    binding.lib()            # raises if liblaa.so is missing: no fallback
+    return binding
+
+
+def dev(a, dtype=None):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to("cuda:0")
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.detach().cpu().numpy()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# a few blocks of 256 threads x 4 coordinates plus a ragged tail
+D_SMALL = 4 * (256 * 9 + 37)
+
+
+def test_philox_words_bit_exact(B):
+    rng = np.random.default_rng(0)
+    cases = [([0, 0, 0, 0], [0, 0]), ([0xFFFFFFFF] * 4, [0xFFFFFFFF] * 2)]
+    cases += [(rng.integers(0, 2**32, 4, dtype=np.uint64).tolist(), rng.integers(0, 2**32, 2, dtype=np.uint64).tolist())
+              for _ in range(20)]
+    for ctr, key in cases:
+        assert np.array_equal(B.debug_philox(ctr, key), oracle.philox4x32_10(ctr, key)), (ctr, key)
+
+
+@pytest.mark.parametrize("W,H,d", [(4, 4, D_SMALL), (8, 8, D_SMALL), (1, 3, 4 * 300), (2, 2, 4 * 1000),
+                                   (3, 5, 4 * 777), (5, 2, 4 * 513), (16, 4, 4 * 2049), (12, 3, 4 * 700),
+                                   (4, 4, 4 * 256 * 3 + 3), (8, 2, 1023), (2, 4, 1)])
+def test_dense_explicit_one_step_and_full_run(B, W, H, d):
+    """Same gradient bits on both sides: <= 1e-6 after one step, <= 1e-5 after T steps with syncs."""
+    say(f"dense explicit W={W} H={H} d={d}")
+    T = 4 * H
+    rng = np.random.default_rng(1000 + W * 31 + H)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    sig = np.power(10.0, rng.uniform(-3, 1, d)).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(dev(x0))
+    sc = parity.Scale(o)
+    for t in range(1, T + 1):
+        G = (rng.standard_normal((W, d)).astype(np.float32) * sig[None, :])
+        o.local_step_dense(G)
+        g.local_step_dense(dev(G))
+        sc.update(o)
+        if t == 1:
+            parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.ONE_STEP, what="one step", scale=sc)
+        if t % H == 0:
+            o.sync(); g.sync()
+        assert g.counters() == (o.t, o.steps_since_sync)
+    e = parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what=f"after {T} steps",
+                            scale=sc)
+    say("   rel err x/acc/snap", e)
+
+
+def test_unaligned_buffers_take_scalar_path(B):
+    import torch
+    W, H, d = 4, 2, 4 * 500
+    rng = np.random.default_rng(5)
+    buf = torch.empty(2 * W * d + d + 16, dtype=torch.float32, device="cuda:0")
+    x = buf[1:1 + W * d].view(W, d)                    # 4-byte but not 16-byte aligned
+    acc = buf[1 + W * d:1 + 2 * W * d].view(W, d)
+    snap = buf[1 + 2 * W * d:1 + 2 * W * d + d]
+    o = Oracle(d, W, H, 0.3, 0.5); o.init_state()
+    g = B.LocalAdaAlter(d, W, H, 0.3, 0.5, x=x, acc=acc, snap=snap); g.init_state()
+    sc = parity.Scale(o)
+    for t in range(1, 5):
+        G = rng.standard_normal((W, d)).astype(np.float32)
+        o.local_step_dense(G); sc.update(o)
+        if t % H == 0:
+            o.sync()
+        g.step_dense(dev(G))
+    parity.assert_state(host(x), host(acc), host(snap), o, parity.FULL_RUN, what="unaligned", scale=sc)
+
+
+def test_fused_step_equals_local_step_plus_sync(B):
+    import torch
+    W, H, d = 8, 3, D_SMALL
+    rng = np.random.default_rng(6)
+    a = B.LocalAdaAlter(d, W, H, 0.5, 1.0); a.init_state()
+    b = B.LocalAdaAlter(d, W, H, 0.5, 1.0); b.init_state()
+    for t in range(1, 3 * H + 1):
+        G = dev(rng.standard_normal((W, d)).astype(np.float32))
+        a.step_dense(G)
+        b.local_step_dense(G)
+        if t % H == 0:
+            b.sync()
+        assert a.counters() == b.counters()
+    torch.cuda.synchronize()
+    assert torch.equal(a.x, b.x) and torch.equal(a.acc, b.acc) and torch.equal(a.snap, b.snap)
+
+
+def test_sync_due_early_sync_and_noop_sync(B):
+    W, H, d = 2, 2, 64
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    G = np.ones((W, d), dtype=np.float32)
+    g.sync()                                         # nothing to do
+    assert g.counters() == (0, 0)
+    g.local_step_dense(dev(G)); g.local_step_dense(dev(G))
+    with pytest.raises(B.LaaError) as ei:
+        g.local_step_dense(dev(G))
+    assert ei.value.code == B.ESYNCDUE
+    g.sync()
+    g.local_step_dense(dev(G)); g.sync()             # early sync, t' restarts
+    g.local_step_dense(dev(G))
+    for _ in range(2):
+        o.local_step_dense(G)
+    o.sync(); o.local_step_dense(G); o.sync(); o.local_step_dense(G)
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.ONE_STEP, what="early sync")
+    with pytest.raises(B.LaaError) as ei:
+        g.local_step_gen()
+    assert ei.value.code == B.EMODE
+
+
+def _gen_scale(a, x, xs, off_scale, noise_scale):
+    """Magnitude of the terms that make up g = a (x - (xstar + off)) + noise_scale n."""
+    return np.abs(a)[None, :] * (np.abs(x) + np.abs(xs)[None, :] + 4 * off_scale) + 5 * noise_scale
+
+
+@pytest.mark.parametrize("mode,off_mode,W,d", [("quad", "none", 4, D_SMALL), ("quad", "array", 4, D_SMALL),
+                                               ("quad", "philox", 8, D_SMALL), ("quad", "philox", 3, 4 * 300 + 2),
+                                               ("noise", "none", 8, D_SMALL), ("noise", "none", 2, 999)])
+def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d):
+    import torch
+    say(f"generator mode={mode} off={off_mode} W={W} d={d}")
+    H, seed = 4, 1234567890123
+    rng = np.random.default_rng(7)
+    a = rng.uniform(0.1, 10, d).astype(np.float32)
+    xs = rng.standard_normal(d).astype(np.float32)
+    off = (0.1 * rng.standard_normal((W, d))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    gm = {"quad": oracle.GEN_QUADRATIC, "noise": oracle.GEN_NOISE}[mode]
+    om = {"none": oracle.OFF_NONE, "array": oracle.OFF_ARRAY, "philox": oracle.OFF_PHILOX}[off_mode]
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    o.set_generator(gm, seed, a, xs, off if off_mode == "array" else None, om, 0.1, 0.1)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(dev(x0))
+    u = B.LocalAdaAlter(d, W, H, 0.5, 1.0); u.init_state(dev(x0))       # unfused twin: generate, then explicit step
+    da, dxs, doff = dev(a), dev(xs), dev(off)
+    for inst in (g, u):
+        inst.set_generator(gm, seed, da, dxs if mode == "quad" else None, doff if off_mode == "array" else None,
+                           om, 0.1, 0.1)
+    for t in range(1, 2 * H + 2):
+        x_before = o.x
+        G_ref = o.gradient(t)
+        G_gpu = host(g.generate_gradient())
+        scale = _gen_scale(a, x_before, xs, 0.1, 0.1) if mode == "quad" else np.abs(a)[None, :] * 5
+        err = np.max(np.abs(G_gpu - G_ref) / scale)
+        assert err <= 1e-6, f"gradient at t={t}: {err:.2e}"
+        Gu = u.generate_gradient()
+        g.step_gen(); u.step_dense(Gu); o.step_gen()
+        torch.cuda.synchronize()
+        assert torch.equal(g.x, u.x) and torch.equal(g.acc, u.acc), f"fused != unfused at t={t}"
+        bar = 1e-5
+        parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, bar, floor_x=1.0, what=f"gen t={t}")
+
+
+def test_generator_statistics_on_device(B):
+    """The device normals themselves: moments over 4M draws (noise mode with a = 1 writes n directly)."""
+    import torch
+    d, W = 1 << 20, 4
+    g = B.LocalAdaAlter(d, W, 4, 0.5, 1.0); g.init_state()
+    ones = torch.ones(d, device="cuda:0")
+    g.set_generator(B.GEN_NOISE, 99, ones)
+    n = host(g.generate_gradient()).astype(np.float64).ravel()
+    N = n.size
+    assert abs(n.mean()) < 4 / np.sqrt(N) and abs(n.var() - 1) < 4 * np.sqrt(2 / N)
+    assert abs(((n - n.mean()) ** 3).mean()) < 4 * np.sqrt(6 / N)
+    assert abs((n ** 4).mean() - 3) < 4 * np.sqrt(96 / N)
+
+
+@pytest.mark.parametrize("W,rows,row_len,k,H", [(3, 1000, 32, 100, 3), (8, 5000, 512, 300, 4), (4, 257, 4, 64, 2),
+                                               (2, 100, 260, 100, 2)])
+def test_sparse_steps_match_oracle_and_dirty_rows_exact(B, W, rows, row_len, k, H):
+    say(f"sparse W={W} rows={rows} row_len={row_len} k={k}")
+    d = rows * row_len
+    rng = np.random.default_rng(11)
+    zipf = wl.ZipfRows(rows, 1.1)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(dev(x0))
+    sc = parity.Scale(o)
+    for t in range(1, 2 * H + 2):
+        idx, vals = wl.sparse_step(zipf, W, k, row_len, 3, t)
+        o.local_step_sparse(idx, vals, row_len)
+        g.local_step_sparse(dev(idx), dev(vals), row_len)
+        sc.update(o)
+        assert np.array_equal(g.dirty_rows(), o.dirty_rows()), f"dirty rows differ at t={t}"
+        if t == 1:
+            parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.ONE_STEP, what="sparse one step",
+                                scale=sc)
+        if t % H == 0:
+            o.sync(); g.sync()
+            assert g.dirty_rows().size == 0
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="sparse run", scale=sc)
+    assert g.counters(with_bad=True)[2] == 0
+
+
+def test_sparse_edge_cases(B):
+    import torch
+    W, rows, row_len, H = 2, 64, 8, 2
+    d = rows * row_len
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    # k = 0: a step that touches nothing still counts as a step
+    g.local_step_sparse(None, None, row_len)
+    o.local_step_sparse(np.zeros((W, 0), np.int32), np.zeros((W, 0, row_len)), row_len)
+    assert g.counters() == (1, 1) and g.dirty_rows().size == 0
+    # out-of-range rows are skipped and counted; valid ones applied
+    idx = np.array([[3, 64, 7], [-1, 5, 63]], dtype=np.int32)
+    vals = np.ones((W, 3, row_len), dtype=np.float32)
+    g.local_step_sparse(dev(idx), dev(vals), row_len)
+    idx_ok = np.array([[3, 7], [5, 63]], dtype=np.int32)
+    o.local_step_sparse(idx_ok, np.ones((W, 2, row_len)), row_len)
+    assert g.counters(with_bad=True) == (2, 0 + 2, 2)
+    assert np.array_equal(g.dirty_rows(), np.array([3, 5, 7, 63], dtype=np.int32))
+    g.sync(); o.sync()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.ONE_STEP, what="sparse edge")
+    # the sparse sync must leave untouched rows alone and equal the dense sync on touched rows
+    x = host(g.x).reshape(W, rows, row_len)
+    assert np.all(x[:, [0, 1, 2, 4, 6, 62]] == 0.0)
+    with pytest.raises(B.LaaError):
+        g.local_step_sparse(dev(idx), dev(vals), 6)            # row_len not a multiple of 4
+    # mixed dense + sparse in one period falls back to the dense mean
+    G = np.random.default_rng(1).standard_normal((W, d)).astype(np.float32)
+    sc = parity.Scale(o)
+    g.local_step_dense(dev(G)); o.local_step_dense(G); sc.update(o)
+    g.local_step_sparse(dev(idx_ok), dev(vals[:, :2]), row_len); o.local_step_sparse(idx_ok, vals[:, :2], row_len)
+    sc.update(o)
+    g.sync(); o.sync()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="mixed period", scale=sc)
+
+
+def test_warmup_learning_rate(B):
+    W, H, d, T = 4, 4, 4 * 300, 12
+    rng = np.random.default_rng(12)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(); o.set_warmup(5)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(); g.set_warmup(5)
+    sc = parity.Scale(o)
+    for t in range(1, T + 1):
+        G = rng.standard_normal((W, d)).astype(np.float32)
+        o.local_step_dense(G); sc.update(o)
+        if t % H == 0:
+            o.sync()
+        g.step_dense(dev(G))
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="warm-up", scale=sc)
+
+
+@pytest.mark.parametrize("W,d", [(4, D_SMALL), (3, 4 * 100 + 1), (8, 4 * 1000)])
+def test_adagrad_and_local_sgd_variants(B, W, d):
+    H, T = 3, 9
+    rng = np.random.default_rng(13)
+    Gs = [rng.standard_normal((W, d)).astype(np.float32) for _ in range(T)]
+    o = Oracle(d, W, 1, 0.3, 0.1, 0.0); o.init_state()
+    g = B.LocalAdaAlter(d, W, 1, 0.3, 0.1, b0=0.0); g.set_algorithm(B.ALGO_DIST_ADAGRAD); g.init_state()
+    sc = parity.Scale(o)
+    for G in Gs:
+        o.adagrad_step_dense(G); g.step_dense(dev(G)); sc.update(o)
+    assert parity.rel_err(host(g.x), o.x, 1e-3, sc.s) <= parity.FULL_RUN
+    assert parity.rel_err(host(g.snap), o.snap, 1e-3) <= parity.FULL_RUN
+    o = Oracle(d, W, H, 0.3, 0.1); o.init_state()
+    g = B.LocalAdaAlter(d, W, H, 0.3, 0.1); g.set_algorithm(B.ALGO_LOCAL_SGD); g.init_state()
+    sc = parity.Scale(o)
+    for t, G in enumerate(Gs):
+        o.localsgd_step_dense(G); g.step_dense(dev(G)); sc.update(o)
+        assert parity.rel_err(host(g.x), o.x, 1e-3, sc.s) <= parity.FULL_RUN, f"local sgd t={t + 1}"
+    with pytest.raises(B.LaaError):
+        g.local_step_dense(dev(Gs[0]))
+
+
+# ------------------------------------------------------------------------------------------ benchmark configurations
+def _quadratic_setup(B, c, n_groups, off_mode="philox"):
+    """GPU instance at the full size of workload c and an oracle that follows a sample of its columns."""
+    cols = wl.column_sample(c.d, n_groups, seed=1)
+    a = wl.curvature(c.d, c.seed, c.a_dist)
+    xs = wl.optimum(c.d, c.seed)
+    om = {"philox": oracle.OFF_PHILOX, "none": oracle.OFF_NONE}[off_mode]
+    o = Oracle(len(cols), c.W, c.H, c.eta, c.eps)
+    o.set_columns(cols); o.init_state()
+    o.set_generator(oracle.GEN_QUADRATIC, c.seed, a[cols], xs[cols], None, om, c.noise_scale, c.off_scale)
+    g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps); g.init_state()
+    g.set_generator(B.GEN_QUADRATIC, c.seed, dev(a), dev(xs), None, om, c.noise_scale, c.off_scale)
+    return cols, o, g
+
+
+def _sampled(t, cols):
+    import torch
+    idx = torch.from_numpy(cols).to("cuda:0")
+    return host(t.index_select(t.dim() - 1, idx))
+
+
+def test_config1_full_run_on_sampled_columns(B):
+    """d=2^20, W=4, H=4, T=64 (the small configuration), full length, oracle on 4096 sampled columns."""
+    c = wl.WORKLOADS["c1"]
+    cols, o, g = _quadratic_setup(B, c, 1024)
+    for t in range(1, c.T + 1):
+        o.step_gen(); g.step_gen()
+        if t in (1, c.H, c.T):
+            e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
+                                    floor_x=1.0, what=f"c1 t={t}")
+            say(f"   c1 t={t} rel err", e)
+    # after the last sync all workers agree exactly, everywhere
+    import torch
+    assert all(torch.equal(g.x[0], g.x[w]) and torch.equal(g.acc[0], g.acc[w]) for w in range(1, c.W))
+    assert torch.equal(g.acc[0], g.snap)
+
+
+def test_config2_two_periods_on_sampled_columns(B):
+    c = wl.WORKLOADS["c2"]
+    cols, o, g = _quadratic_setup(B, c, 1024)
+    for t in range(1, 2 * c.H + 2):
+        o.step_gen(); g.step_gen()
+    e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
+                            floor_x=1.0, what="c2")
+    say("   c2 rel err", e)
+
+
+def test_config5_headline_size_two_periods_on_sampled_columns(B):
+    """d=400M, W=8, H=16 in the launch configuration the benchmark times (fused step, Philox offsets)."""
+    import torch
+    c = wl.WORKLOADS["c5"]
+    cols, o, g = _quadratic_setup(B, c, 512)
+    for t in range(1, 2 * c.H + 1):
+        o.step_gen(); g.step_gen()
+        if t == 1:
+            parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
+                                floor_x=1.0, what="c5 t=1")
+    e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
+                            floor_x=1.0, what="c5")
+    say("   c5 rel err", e)
+    # properties that hold at any size: consensus after the sync, snap == acc, accumulator >= b0^2
+    assert torch.equal(g.x[0], g.x[c.W - 1]) and torch.equal(g.acc[3], g.snap)
+    assert float(g.snap.min()) >= 1.0
+    del g
+    torch.cuda.empty_cache()
+
+
+def test_config3_explicit_gradient_pool(B):
+    """d=100M, W=8: dense gradients N(0, sigma_j^2) precomputed into HBM, streamed by the explicit-gradient step."""
+    import torch
+    c = wl.WORKLOADS["c3"]
+    H = 4
+    sig = wl.sigma(c.d, c.seed)
+    cols = wl.column_sample(c.d, 512, seed=2)
+    g = B.LocalAdaAlter(c.d, c.W, H, c.eta, c.eps); g.init_state()
+    g.set_generator(B.GEN_NOISE, c.seed, dev(sig))
+    o = Oracle(len(cols), c.W, H, c.eta, c.eps); o.set_columns(cols); o.init_state()
+    o.set_generator(oracle.GEN_NOISE, c.seed, sig[cols])
+    pool = torch.empty((c.W, c.d), dtype=torch.float32, device="cuda:0")
+    sc = parity.Scale(o)
+    for t in range(1, 2 * H + 1):
+        g.generate_gradient(pool)                       # materialise this iteration's gradient, then stream it
+        G_ref = o.gradient(t)
+        G_gpu = _sampled(pool, cols)
+        assert np.max(np.abs(G_gpu - G_ref) / (np.abs(sig[cols])[None, :] * 5)) <= 1e-6
+        g.step_dense(pool)                              # identical gradient bits from here on
+        o.local_step_dense(G_gpu); sc.update(o)
+        if t % H == 0:
+            o.sync()
+        if t == 1:
+            parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o,
+                                parity.ONE_STEP, what="c3 one step", scale=sc)
+    parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, parity.FULL_RUN,
+                        what="c3", scale=sc)
+    del g, pool
+    torch.cuda.empty_cache()
+
+
+def test_config4_embedding_table_sampled_rows(B):
+    """800,000 x 512 table, W=8, k=8192 Zipf(1.1) rows per worker and step; oracle follows a sample of rows."""
+    import torch
+    c = wl.WORKLOADS["c4"]
+    H = 4
+    zipf = wl.ZipfRows(c.rows, c.zipf_s)
+    g = B.LocalAdaAlter(c.d, c.W, H, c.eta, c.eps); g.init_state()
+    steps = [wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, c.val_sigma) for t in range(1, H + 2)]
+    # sample: the 8 hottest rows, 24 rows drawn from those touched, 8 rows never touched
+    touched = np.unique(np.concatenate([s[0].ravel() for s in steps]))
+    rng = np.random.default_rng(4)
+    never = np.setdiff1d(np.arange(c.rows), touched)[:8]
+    sample = np.unique(np.concatenate([np.arange(8), rng.choice(touched, 24, replace=False), never]))
+    remap = -np.ones(c.rows, dtype=np.int64); remap[sample] = np.arange(sample.size)
+    o = Oracle(sample.size * c.row_len, c.W, H, c.eta, c.eps); o.init_state()
+    union = set()
+    sc = parity.Scale(o)
+    for t, (idx, vals) in enumerate(steps, start=1):
+        g.local_step_sparse(dev(idx), dev(vals), c.row_len)
+        # the oracle sees each worker's sampled rows only (padded per worker to a common k with zero rows is not
+        # needed: a dense step on the scattered gradient is the definition)
+        G = np.zeros((c.W, sample.size, c.row_len))
+        for w in range(c.W):
+            m = remap[idx[w]]
+            G[w, m[m >= 0]] = vals[w][m >= 0]
+        o.local_step_dense(G.reshape(c.W, -1)); sc.update(o)
+        union |= set(idx.ravel().tolist())
+        if t == 1:
+            assert np.array_equal(g.dirty_rows(), np.array(sorted(union), dtype=np.int32))
+        if t % H == 0:
+            assert np.array_equal(g.dirty_rows(), np.array(sorted(union), dtype=np.int32))
+            g.sync(); o.sync(); union = set()
+    cols = (sample[:, None] * c.row_len + np.arange(c.row_len)[None, :]).reshape(-1)
+    parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, parity.FULL_RUN,
+                        what="c4", scale=sc)
+    assert g.counters(with_bad=True)[2] == 0
+    # rows nobody touched keep their initial state on every worker
+    nv = (never[:, None] * c.row_len + np.arange(c.row_len)[None, :]).reshape(-1)
+    assert np.all(_sampled(g.x, nv) == 0.0) and np.all(_sampled(g.acc, nv) == 1.0)
+    del g
+    torch.cuda.empty_cache()
