@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Throughput of the Local AdaAlter hot path on one MI355X.
+
+A *step* is one iteration of Algorithm 3 (arXiv 1911.09030) for all W workers: the fused
+gradient + parameter update + accumulator update and, on every H-th iteration, the averaging
+of x and B^2 over the worker axis.  The default workload is the headline configuration
+(d = 400M fp32 parameters, W = 8, H = 16, gradients fused in-kernel from a Philox seed).
+
+Prints ONE JSON line: whole-job element-updates/s with inputs resident in HBM, the HBM roofline
+of the dominant kernel (algorithmic bytes per launch / its average duration from HIP events on
+the launch stream), and the CPU oracle timed on the host on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=256)
+    p.add_argument("--warmup", type=int, default=16)
+    p.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
+    p.add_argument("--H", type=int, default=0, help="override the sync period (c3 sweep)")
+    p.add_argument("--offsets", default="philox", choices=["philox", "array", "none"],
+                   help="per-worker optimum offsets: regenerated in-kernel, read from HBM, or absent")
+    p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
+    p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
+    p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--calibrate-copy", type=int, default=0,
+                   help="after the run, launch the plain copy kernel this many times over one row of d floats "
+                        "(a known volume for scaling profiler byte counters)")
+    p.add_argument("--cpu-sample-d", type=int, default=524_288)
+    return p.parse_args()
+
+
+def traffic_from_profile(kernel_tag: str):
+    """Last profiled HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated), if recorded."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{kernel_tag}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(c, sample_d, offsets):
+    """The oracle as it stands (single thread, fp64) on a column slice of the same workload: one sync period."""
+    import numpy as np
+    import oracle
+    from paper_1911_09030_amd import workloads as wl
+    cols = np.arange(sample_d, dtype=np.int64)
+    a = wl.curvature(sample_d, c.seed, c.a_dist)
+    xs = wl.optimum(sample_d, c.seed)
+    o = oracle.Oracle(sample_d, c.W, c.H, c.eta, c.eps)
+    o.set_columns(cols)
+    o.init_state()
+    om = {"philox": oracle.OFF_PHILOX, "none": oracle.OFF_NONE, "array": oracle.OFF_ARRAY}[offsets]
+    off = wl.offsets(sample_d, c.W, c.seed, c.off_scale) if offsets == "array" else None
+    o.set_generator(oracle.GEN_QUADRATIC, c.seed, a, xs, off, om, c.noise_scale, c.off_scale)
+    t0 = time.perf_counter()
+    for _ in range(c.H):
+        o.step_gen()
+    dt = time.perf_counter() - t0
+    return {"value": c.W * sample_d * c.H / dt, "unit": "element-updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {sample_d} columns of {c.name}, W={c.W}, one sync period of H={c.H} steps, fp64, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the W workers are a worker axis in one GPU's HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1911_09030_amd import binding as B, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = torch.device("cuda:0")
+    c = wl.WORKLOADS[args.workload]
+    H = args.H or c.H
+    K, Wm = args.steps, args.warmup
+    d, W = c.d, c.W
+
+    pitch = args.pitch or None
+    extra = []          # further state machines stepped in the same iteration (c4's dense blocks)
+    if c.kind == "quadratic":
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+        g.init_state()
+        a = torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)).to(dev)
+        xs = torch.from_numpy(wl.optimum(d, c.seed)).to(dev)
+        off = None
+        if args.offsets == "array":
+            off = g.rows()
+            for w in range(W):      # inputs only: N(0, off_scale^2) drawn on the device, one worker row at a time
+                off[w].normal_(0.0, c.off_scale)
+        om = {"philox": B.OFF_PHILOX, "array": B.OFF_ARRAY, "none": B.OFF_NONE}[args.offsets]
+        g.set_generator(B.GEN_QUADRATIC, c.seed, a, xs, off, om, c.noise_scale, c.off_scale)
+        step_bytes = (16 * W + 12 + (4 * W if off is not None else 0)) * d
+        kernel_tag = f"step_kernel_{c.name}"
+        if args.unfused_sync:
+            def do_step(t):
+                g.local_step_gen()
+                if t % H == 0:
+                    g.sync()
+        else:
+            def do_step(t):
+                g.step_gen()
+        updates_per_step = W * d
+    elif c.kind == "explicit":
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+        g.init_state()
+        sig = torch.from_numpy(wl.sigma(d, c.seed)).to(dev)
+        g.set_generator(B.GEN_NOISE, c.seed, sig)
+        P = 4
+        pool = [g.rows() for _ in range(P)]
+        for p in range(P):           # precompute the gradient pool in HBM; the timed loop streams it
+            g.generate_gradient(pool[p])
+            g.step_dense(pool[p])    # advance t so each pool entry uses another iteration's noise
+        g.init_state()
+        step_bytes = (20 * W + 4) * d
+        kernel_tag = f"step_kernel_{c.name}"
+
+        def do_step(t):
+            g.step_dense(pool[t % P])
+        updates_per_step = W * d
+    else:  # embedding table with row-sparse gradients + dense LSTM blocks
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+        g.init_state()
+        zipf = wl.ZipfRows(c.rows, c.zipf_s)
+        P = 16
+        idx_pool = [torch.from_numpy(wl.sparse_step(zipf, W, c.k, c.row_len, c.seed, t, with_vals=False)[0]).to(dev)
+                    for t in range(P)]
+        vals_pool = [torch.randn((W, c.k, c.row_len), dtype=torch.float32, device=dev) * c.val_sigma for _ in range(4)]
+        dd = sum(r * q for r, q in c.dense_blocks)
+        gd = B.LocalAdaAlter(dd, W, H, c.eta, c.eps, pitch=pitch)
+        gd.init_state()
+        sigd = torch.from_numpy(wl.sigma(dd, c.seed)).to(dev)
+        gd.set_generator(B.GEN_NOISE, c.seed, sigd)
+        extra.append(gd)
+        step_bytes = W * c.k * (c.row_len * 24 + 4)
+        kernel_tag = f"sparse_step_kernel_{c.name}"
+
+        def do_step(t):
+            g.step_sparse(idx_pool[t % P], vals_pool[t % 4], c.row_len)
+            gd.step_gen()
+        updates_per_step = W * c.k * c.row_len + W * dd
+    if args.tile:
+        g.set_tile(args.tile)
+
+    # warm-up (untimed), then realign to a period boundary so the timed region holds K/H syncs
+    t = 0
+    for _ in range(Wm):
+        t += 1
+        do_step(t)
+    while t % H:
+        t += 1
+        do_step(t)
+    torch.cuda.synchronize()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(K):
+        t += 1
+        do_step(t)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
+    # the dominant kernel is the non-sync step; sync iterations are the ones with (i+1) % H == 0
+    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0] or per_step_ms
+    sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
+    kern_ms = sum(plain) / len(plain)
+    achieved = step_bytes / (kern_ms * 1e-3) / 1e9
+    value = updates_per_step * K / wall
+
+    assert bool(torch.isfinite(g.x[0, :4096]).all()), "non-finite parameters after the run"
+    for _ in range(args.calibrate_copy):          # reads 4d bytes, writes 4d bytes
+        B.debug_copy(g.acc[0], g.x[0])
+    torch.cuda.synchronize()
+
+    out = {
+        "metric": "element-updates/sec and achieved HBM GB/s (% of peak), step+sync, 1 GPU",
+        "value": value, "unit": "element-updates/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
+                               f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
+                               f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
+                               f"row_pitch={g.pitch}",
+                   "syncs_in_timed_region": len(sync_it),
+                   "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
+                   "method_bytes_per_element_update": 16 + 4 / W + (16 * W + 4) / (W * H)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(kernel_tag),
+                     "kernel": kernel_tag.rsplit("_", 1)[0], "kernel_ms": kern_ms,
+                     "algorithmic_bytes_per_launch": step_bytes},
+    }
+    if not args.no_cpu_baseline and c.kind == "quadratic":
+        out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -21,7 +21,8 @@
  *     without waiting, except the getters that copy to host memory, which
  *     synchronise that stream.
  *   - Layout: x and acc are [W][d] row-major fp32 (worker-major, coordinate
- *     contiguous); snap, a, xstar are [d] fp32.  64-bit indexing throughout.
+ *     contiguous; optionally with a row pitch, see laa_attach_pitched); snap,
+ *     a, xstar are [d] fp32.  64-bit indexing throughout.
  *     Rows must be 4-byte aligned; the vectorised kernels are used when all
  *     base pointers are 16-byte aligned and d % 4 == 0, a scalar path otherwise.
  *   - A handle is not thread-safe; use one handle from one thread at a time.
@@ -92,6 +93,13 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch);
  * last sync), and the HIP stream (hipStream_t, may be null for the default
  * stream) on which all work is enqueued. */
 int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream);
+
+/* The same with rows `pitch` >= d elements apart: x, acc (and every other [W][.] array handed to
+ * this handle: explicit gradients, stored offsets, laa_generate_gradient's output) are [W][pitch]
+ * with the first d entries of each row used; the padding is never read or written.  For callers
+ * whose per-worker arrays are padded or are slices of a larger buffer.  The 16-byte path needs
+ * pitch % 4 == 0. */
+int laa_attach_pitched(laa_handle h, float *x, float *acc, float *snap, int64_t pitch, void *hip_stream);
 
 /* Algorithm 3, Initialize: x[w] = x0 for every w (x0 device [d], or null for
  * zero), acc = snap = b0^2, counters reset, dirty rows cleared. */

@@ -21,7 +21,7 @@ ALGO_LOCAL_ADAALTER, ALGO_DIST_ADAGRAD, ALGO_LOCAL_SGD = 0, 1, 2
 
 EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
-    "laa_set_tile", "laa_attach", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
+    "laa_set_tile", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_get_dirty_rows", "laa_bytes_moved",
     "laa_debug_philox", "laa_debug_copy",
@@ -56,6 +56,7 @@ def lib():
         "laa_set_algorithm": [vp, i32],
         "laa_set_tile": [vp, i32],
         "laa_attach": [vp, vp, vp, vp, vp],
+        "laa_attach_pitched": [vp, vp, vp, vp, i64, vp],
         "laa_init_state": [vp, vp],
         "laa_local_step_dense": [vp, vp],
         "laa_set_generator": [vp, i32, u64, vp, vp, vp, i32, f32, f32],
@@ -98,10 +99,14 @@ def _dev_ptr(t, dtype=None):
 class LocalAdaAlter:
     """One optimizer state (x, acc [W][d]; snap [d]) on the current device and stream.
 
-    Method names mirror the C entry points without the ``laa_`` prefix.
+    Method names mirror the C entry points without the ``laa_`` prefix.  With ``pitch`` > d the
+    rows of x, acc and of every [W][.] array passed in are ``pitch`` elements apart
+    (``self.x`` / ``self.acc`` are then [W][d] views of [W][pitch] buffers, and ``rows()`` makes
+    such a buffer for gradients and offsets).
     """
 
-    def __init__(self, d, W, H, eta, eps, b0=None, device="cuda:0", x=None, acc=None, snap=None, stream=None):
+    def __init__(self, d, W, H, eta, eps, b0=None, device="cuda:0", x=None, acc=None, snap=None, stream=None,
+                 pitch=None):
         import torch
         self.torch = torch
         self.L = lib()
@@ -113,13 +118,33 @@ class LocalAdaAlter:
             _check(self.L.laa_set_b0(self.h, float(b0)))
         self.device = torch.device(device)
         f = dict(dtype=torch.float32, device=self.device)
-        self.x = x if x is not None else torch.empty((self.W, self.d), **f)
-        self.acc = acc if acc is not None else torch.empty((self.W, self.d), **f)
+        self.pitch = int(pitch) if pitch else (x.stride(0) if x is not None and x.dim() == 2 else self.d)
+        self.x = x if x is not None else self.rows()
+        self.acc = acc if acc is not None else self.rows()
         self.snap = snap if snap is not None else torch.empty((self.d,), **f)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self._keep = []
-        _check(self.L.laa_attach(self.h, _dev_ptr(self.x, torch.float32), _dev_ptr(self.acc, torch.float32),
-                                 _dev_ptr(self.snap, torch.float32), C.c_void_p(self.stream.cuda_stream)))
+        _check(self.L.laa_attach_pitched(self.h, self._rows_ptr(self.x), self._rows_ptr(self.acc),
+                                         _dev_ptr(self.snap, torch.float32), self.pitch,
+                                         C.c_void_p(self.stream.cuda_stream)))
+
+    def rows(self, src=None):
+        """A [W][d] device array whose rows are ``pitch`` apart (a view of a [W][pitch] buffer), optionally
+        filled from ``src`` (a [W][d] tensor)."""
+        torch = self.torch
+        buf = torch.empty((self.W, self.pitch), dtype=torch.float32, device=self.device)
+        view = buf[:, :self.d]
+        if src is not None:
+            view.copy_(src)
+        return view
+
+    def _rows_ptr(self, t):
+        if t is None:
+            return None
+        if (not t.is_cuda or t.dtype != self.torch.float32 or t.shape != (self.W, self.d) or t.stride(1) != 1
+                or (self.W > 1 and t.stride(0) != self.pitch)):
+            raise ValueError(f"expected a float32 device array [W={self.W}][d={self.d}] with row pitch {self.pitch}")
+        return C.c_void_p(t.data_ptr())
 
     def close(self):
         if getattr(self, "h", None):
@@ -145,14 +170,14 @@ class LocalAdaAlter:
         f32 = self.torch.float32
         self._keep = [a, xstar, off]       # the library reads these arrays on every generator step
         _check(self.L.laa_set_generator(self.h, int(mode), int(seed), _dev_ptr(a, f32), _dev_ptr(xstar, f32),
-                                        _dev_ptr(off, f32), int(off_mode), float(noise_scale), float(off_scale)))
+                                        self._rows_ptr(off), int(off_mode), float(noise_scale), float(off_scale)))
 
     # steps ---------------------------------------------------------------------------------
     def local_step_dense(self, grads):
-        _check(self.L.laa_local_step_dense(self.h, _dev_ptr(grads, self.torch.float32)))
+        _check(self.L.laa_local_step_dense(self.h, self._rows_ptr(grads)))
 
     def step_dense(self, grads):
-        _check(self.L.laa_step_dense(self.h, _dev_ptr(grads, self.torch.float32)))
+        _check(self.L.laa_step_dense(self.h, self._rows_ptr(grads)))
 
     def local_step_gen(self):
         _check(self.L.laa_local_step_gen(self.h))
@@ -162,8 +187,8 @@ class LocalAdaAlter:
 
     def generate_gradient(self, out=None):
         if out is None:
-            out = self.torch.empty((self.W, self.d), dtype=self.torch.float32, device=self.device)
-        _check(self.L.laa_generate_gradient(self.h, _dev_ptr(out, self.torch.float32)))
+            out = self.rows()
+        _check(self.L.laa_generate_gradient(self.h, self._rows_ptr(out)))
         return out
 
     def local_step_sparse(self, idx, vals, row_len):

@@ -11,7 +11,7 @@
 #include <new>
 
 struct laa_ctx {
-    int64_t d = 0;
+    int64_t d = 0, pitch = 0;
     int32_t W = 0, H = 0;
     double eta = 0, eps = 0, b0 = 1.0;
     int64_t warmup_steps = 0;
@@ -20,6 +20,7 @@ struct laa_ctx {
     hipStream_t stream = nullptr;
     bool attached = false, vec4 = false, gen_aligned16 = true;
     int32_t wt = 1;
+    laa::Tiling tiling;
     int64_t t = 0;          // iterations done
     int32_t s = 0;          // local steps since the last sync (t' - 1 before a step)
     // generator
@@ -143,7 +144,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.grads = kind == STEP_DENSE ? grads : nullptr;
     a.a = h->a; a.xstar = h->xstar; a.off = h->off;
     a.grad_out = nullptr;
-    a.d = h->d; a.W = h->W;
+    a.d = h->d; a.pitch = h->pitch; a.W = h->W;
     a.eta = eta_at(h, h->t + 1);
     const float eps2 = (float)(h->eps * h->eps);
     a.eps2 = eps2;
@@ -156,6 +157,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
     a.algo = h->algo;
     a.wt = h->wt;
+    a.tiling = h->tiling;
     a.vec4 = h->vec4 && (kind == STEP_DENSE ? aligned(grads, 16) : h->gen_aligned16);
     if (!a.vec4) a.wt = 1;
 
@@ -249,14 +251,21 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch)
 
 int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream)
 {
+    return laa_attach_pitched(h, x, acc, snap, h ? h->d : 0, hip_stream);
+}
+
+int laa_attach_pitched(laa_handle h, float *x, float *acc, float *snap, int64_t pitch, void *hip_stream)
+{
     if (!h) return fail(LAA_EINVAL, "null handle");
+    if (pitch < h->d) return fail(LAA_EINVAL, "pitch %lld is smaller than d %lld", (long long)pitch, (long long)h->d);
     if (!x || !acc || !snap) return fail(LAA_EINVAL, "null state pointer");
     if (!aligned(x, 4) || !aligned(acc, 4) || !aligned(snap, 4)) return fail(LAA_EALIGN, "state pointer not 4-byte aligned");
     int n = 0;
     if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) return fail(LAA_ENODEVICE, "no HIP device available");
     h->x = x; h->acc = acc; h->snap = snap;
     h->stream = static_cast<hipStream_t>(hip_stream);
-    h->vec4 = h->d % 4 == 0 && aligned(x, 16) && aligned(acc, 16) && aligned(snap, 16);
+    h->pitch = pitch;
+    h->vec4 = h->d % 4 == 0 && pitch % 4 == 0 && aligned(x, 16) && aligned(acc, 16) && aligned(snap, 16);
     h->attached = true;
     return LAA_OK;
 }
@@ -266,7 +275,7 @@ int laa_init_state(laa_handle h, const float *x0)
     int rc = check_ready(h);
     if (rc != LAA_OK) return rc;
     const float b0sq = (float)(h->b0 * h->b0);
-    hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->W, h->stream);
+    hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "init kernel launch");
     h->t = 0; h->s = 0; h->bytes = 0; h->sparse_only_since_sync = true;
     return clear_dirty(h);
@@ -308,13 +317,14 @@ int laa_generate_gradient(laa_handle h, float *out)
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
     a.a = h->a; a.xstar = h->xstar; a.off = h->off;
     a.grad_out = out;
-    a.d = h->d; a.W = h->W;
+    a.d = h->d; a.pitch = h->pitch; a.W = h->W;
     a.noise_scale = h->noise_scale; a.off_scale = h->off_scale;
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.t_lo = (uint32_t)(h->t + 1);
     a.grad_source = h->gen_mode; a.off_source = h->off_mode;
     a.vec4 = h->vec4 && h->gen_aligned16 && aligned(out, 16);
     a.wt = a.vec4 ? h->wt : 1;
+    a.tiling = h->tiling;
     hipError_t e = laa::launch_step(a, h->stream);
     return e == hipSuccess ? LAA_OK : hip_fail(e, "gradient kernel launch");
 }
@@ -328,7 +338,8 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     if (row_len <= 0 || row_len % 4 != 0) return fail(LAA_EINVAL, "row_len must be a positive multiple of 4");
     if (h->d % row_len != 0) return fail(LAA_EINVAL, "d is not a multiple of row_len");
     if (k > 0 && (!idx || !vals)) return fail(LAA_EINVAL, "null idx/vals");
-    if (!aligned(h->x, 16) || !aligned(h->acc, 16) || !aligned(h->snap, 16) || (k > 0 && !aligned(vals, 16)))
+    if (!aligned(h->x, 16) || !aligned(h->acc, 16) || !aligned(h->snap, 16) || (k > 0 && !aligned(vals, 16)) ||
+        h->pitch % 4 != 0)
         return fail(LAA_EALIGN, "sparse path needs 16-byte aligned x, acc, snap, vals");
     if (k > 0 && !aligned(idx, 4)) return fail(LAA_EALIGN, "idx not 4-byte aligned");
     if (h->s >= h->H)
@@ -338,7 +349,7 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     laa::SparseArgs a{};
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
     a.idx = idx; a.vals = vals; a.dirty = h->dirty; a.bad = h->bad;
-    a.d = h->d; a.n_rows = h->n_rows; a.W = h->W; a.k = k; a.row_len = row_len;
+    a.d = h->d; a.pitch = h->pitch; a.n_rows = h->n_rows; a.W = h->W; a.k = k; a.row_len = row_len;
     a.eta = eta_at(h, h->t + 1);
     a.pad = (float)(h->s + 1) * (float)(h->eps * h->eps);
     hipError_t e = laa::launch_sparse_step(a, h->stream);
@@ -360,10 +371,10 @@ int laa_sync(laa_handle h)
     if (h->dirty && h->sparse_only_since_sync && !x_only) {
         e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
-        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->d, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
-        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->stream);
+        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->tiling, h->stream);
         if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
         h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
     }

@@ -10,9 +10,18 @@ enum GradSource { GRAD_EXPLICIT = 0, GRAD_QUADRATIC = 1, GRAD_NOISE = 2 };
 enum OffsetSource { OFFSET_NONE = 0, OFFSET_ARRAY = 1, OFFSET_PHILOX = 2 };
 enum Algo { ALGO_LOCAL_ADAALTER = 0, ALGO_DIST_ADAGRAD = 1, ALGO_LOCAL_SGD = 2 };
 
+// How thread blocks are mapped to columns: each block walks tiles_per_block consecutive tiles, and blocks are
+// dealt so that each of `xcds` dies owns one contiguous range.  n_chunks / chunks_per_xcd are filled by the launcher.
+struct Tiling {
+    int32_t tiles_per_block = 1;
+    int32_t xcds = 1;
+    int64_t n_chunks = 0;
+    int64_t chunks_per_xcd = 0;
+};
+
 struct StepArgs {
-    float *x;            // [W][d]
-    float *acc;          // [W][d]
+    float *x;            // [W][pitch], d used
+    float *acc;          // [W][pitch]
     float *snap;         // [d]
     const float *grads;  // [W][d] explicit gradients, or null
     const float *a;      // [d]
@@ -20,6 +29,7 @@ struct StepArgs {
     const float *off;    // [W][d]
     float *grad_out;     // [W][d]: write the generated gradient here instead of stepping
     int64_t d;
+    int64_t pitch;       // elements between consecutive workers' rows of x, acc, grads, off, grad_out (>= d)
     int32_t W;
     float eta;           // eta_t of this iteration
     float pad;           // t' * eps^2
@@ -31,14 +41,15 @@ struct StepArgs {
     bool sync;           // average over the worker axis in the same pass
     bool vec4;           // pointers 16-byte aligned and d % 4 == 0
     int32_t wt;          // workers loaded per batch (1, 2, 4 or 8; must divide W)
+    Tiling tiling;
     int32_t algo;
 };
 
 hipError_t launch_step(const StepArgs &a, hipStream_t s);
-hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int32_t W, bool vec4, int32_t wt, bool x_only,
-                       hipStream_t s);
-hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int32_t W,
-                       hipStream_t s);
+hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
+                       bool x_only, Tiling tl, hipStream_t s);
+hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
+                       int32_t W, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
 
 struct SparseArgs {
@@ -48,6 +59,7 @@ struct SparseArgs {
     uint32_t *dirty;     // bitmap, one bit per row
     unsigned long long *bad; // count of skipped out-of-range indices
     int64_t d;
+    int64_t pitch;
     int64_t n_rows;
     int32_t W, k, row_len;
     float eta, pad;
@@ -56,7 +68,7 @@ hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s);
 // bitmap -> ascending row list (device) + count (device); scratch holds one uint32 per 1024 bitmap words (+1)
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s);
-hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t d, int32_t W, int32_t row_len,
+hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t row_len,
                             const int32_t *list, const uint32_t *count, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
 hipError_t debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);

@@ -19,7 +19,20 @@ namespace laa {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-static constexpr int BLOCK = 256;
+#ifndef LAA_BLOCK
+#define LAA_BLOCK 64         // threads per block of the dense streaming kernels
+#endif
+#ifndef LAA_NT_LOAD
+#define LAA_NT_LOAD true     // non-temporal loads of streamed state and gradients
+#endif
+#ifndef LAA_NT_STORE
+#define LAA_NT_STORE true    // non-temporal stores of streamed state
+#endif
+// Dense kernels run one wavefront per thread block: with 16 to 35 independent 16-byte streams per thread the
+// finest dispatch granularity measured fastest (64 > 128 > 256 > 512 threads, about 5 % end to end at d = 4e8).
+static constexpr int DBLOCK = LAA_BLOCK;
+static constexpr int BLOCK = 256;   // bookkeeping kernels (init, fill, sparse rows, bitmap compaction)
+static constexpr bool NT_LD = LAA_NT_LOAD, NT_ST = LAA_NT_STORE;
 
 // ------------------------------------------------------------------------------------------
 // small vector pack: VEC = 4 (16-byte accesses) or VEC = 1 (fallback for unaligned / d % 4 != 0)
@@ -49,8 +62,32 @@ template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const P
 }
 
 // ------------------------------------------------------------------------------------------
+// Thread block -> columns.  A tile is DBLOCK * VEC consecutive columns (one group per thread).  A thread block
+// walks a chunk of tiles_per_block consecutive tiles, and chunks are dealt so that the thread blocks that land
+// on the same XCD (the hardware deals consecutive block ids round-robin over the XCDs) own one contiguous range
+// of columns: each XCD then streams through its own slice of every array, which keeps the pages and cache lines
+// it touches at any moment few and dense.
+template <int VEC, typename F> __device__ __forceinline__ void for_each_tile(int64_t d, const Tiling &tl, F body)
+{
+    int64_t chunk = blockIdx.x;
+    if (tl.xcds > 1) {
+        const int64_t x = chunk % tl.xcds, i = chunk / tl.xcds;
+        chunk = x * tl.chunks_per_xcd + i;
+        if (chunk >= tl.n_chunks) return;
+    }
+    int64_t j = (chunk * tl.tiles_per_block * DBLOCK + threadIdx.x) * VEC;
+    for (int32_t it = 0; it < tl.tiles_per_block && j < d; ++it, j += DBLOCK * VEC) body(j);
+}
+
+// ------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): per round hi0:lo0 = M0*c0, hi1:lo1 = M1*c2,
 // (c0,c1,c2,c3) <- (hi1^c1^k0, lo1, hi0^c3^k1, lo0); the key advances by the Weyl constants.
+// a ^ b ^ c in one VALU operation (three-input bitwise op with truth table 0x96)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
                                               uint32_t k1, uint32_t (&r)[4])
 {
@@ -58,8 +95,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int i = 0; i < 10; ++i) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
         c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
         k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
     }
@@ -70,8 +107,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 __device__ __forceinline__ float u01(uint32_t r) { return fmaf((float)(r >> 9), 0x1p-23f, 0x1p-24f); }
 
 // Four standard normals for the coordinates 4*qa .. 4*qa+3 of worker w at iteration word t on a stream.
-// Box-Muller on (u0,u1) and (u2,u3); the angle is taken in half-turns (2*u exact) so that no
-// rounding of 2*pi*u enters.
+// Box-Muller on (u0,u1) and (u2,u3).
 __device__ __forceinline__ void normals4(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream, uint64_t qa, uint32_t w,
                                          uint32_t t, float (&n)[4])
 {
@@ -80,11 +116,12 @@ __device__ __forceinline__ void normals4(uint32_t seed_lo, uint32_t seed_hi, uin
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const float u0 = u01(r[2 * p]), u1 = u01(r[2 * p + 1]);
-        const float rad = sqrtf(-2.0f * logf(u0));
-        float sn, cs;
-        sincospif(2.0f * u1, &sn, &cs);
-        n[2 * p] = rad * cs;
-        n[2 * p + 1] = rad * sn;
+        // sqrt(-2 ln u0) = sqrt(-2 ln2 * log2 u0); u0 >= 2^-24 is a normal number, so the bare hardware
+        // log2 / sqrt apply (relative error 1.4e-7 over all 2^23 inputs); the hardware sine and cosine take
+        // their argument in turns, which is u1 itself (absolute error 1.3e-7 over all 2^23 inputs).
+        const float rad = __builtin_amdgcn_sqrtf(__builtin_amdgcn_logf(u0) * -1.3862943611198906f);
+        n[2 * p] = rad * __builtin_amdgcn_cosf(u1);
+        n[2 * p + 1] = rad * __builtin_amdgcn_sinf(u1);
     }
 }
 
@@ -93,13 +130,12 @@ static constexpr uint32_t STREAM_OFFSET = 2, STREAM_NOISE = 3;
 // Gradient of worker w for the VEC coordinates starting at j, evaluated at xv (the worker's x before the step).
 //   quadratic: g = a (x - (xstar + off)) + noise_scale n        noise: g = a n
 template <int VEC, int GS, int OS>
-__device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int32_t w, const Pack<VEC> &xv,
-                                              const Pack<VEC> &av, const Pack<VEC> &xs)
+__device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int64_t row, int32_t w,
+                                              const Pack<VEC> &xv, const Pack<VEC> &av, const Pack<VEC> &xs)
 {
     Pack<VEC> g;
-    const int64_t row = (int64_t)w * a.d + j;
     if constexpr (GS == GRAD_EXPLICIT) {
-        g = ld<VEC, true>(a.grads + row);
+        g = ld<VEC, NT_LD>(a.grads + row);
     } else {
         const uint64_t qa = (uint64_t)j >> 2;
         float n[4];
@@ -110,7 +146,7 @@ __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int3
         } else {
             Pack<VEC> o;
             if constexpr (OS == OFFSET_ARRAY) {
-                o = ld<VEC, true>(a.off + row);
+                o = ld<VEC, NT_LD>(a.off + row);
             } else if constexpr (OS == OFFSET_PHILOX) {
                 float m[4];
                 normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, (uint32_t)w, 0u, m);
@@ -152,10 +188,8 @@ template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const P
 //   SYNC: x, B2 <- mean over workers of y, A2; B2_sync <- that mean      (Synchronize branch)
 //   GRAD_ONLY: write g and change nothing (used to materialise gradients)
 template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
-__global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs a)
+__device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j)
 {
-    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (j >= a.d) return;
 
     Pack<VEC> av, xs, step;
     if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
@@ -174,16 +208,16 @@ __global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs a)
         Pack<VEC> xv[WT], bv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            const int64_t row = (int64_t)(w0 + i) * a.d + j;
-            if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, true>(a.x + row);
-            if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, true>(a.acc + row);
+            const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
+            if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, NT_LD>(a.x + row);
+            if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, NT_LD>(a.acc + row);
         }
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            const int64_t row = (int64_t)(w0 + i) * a.d + j;
-            const Pack<VEC> g = gradient<VEC, GS, OS>(a, j, w0 + i, xv[i], av, xs);
+            const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
+            const Pack<VEC> g = gradient<VEC, GS, OS>(a, j, row, w0 + i, xv[i], av, xs);
             if constexpr (GRAD_ONLY) {
-                st<VEC, true>(a.grad_out + row, g);
+                st<VEC, NT_ST>(a.grad_out + row, g);
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
@@ -191,8 +225,8 @@ __global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs a)
                     bv[i].v[e] = fmaf(g.v[e], g.v[e], bv[i].v[e]);
                 }
                 if constexpr (!SYNC) {
-                    st<VEC, true>(a.x + row, xv[i]);
-                    st<VEC, true>(a.acc + row, bv[i]);
+                    st<VEC, NT_ST>(a.x + row, xv[i]);
+                    st<VEC, NT_ST>(a.acc + row, bv[i]);
                 }
             }
         }
@@ -207,21 +241,25 @@ __global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs a)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
         for (int32_t w = 0; w < a.W; ++w) {
-            const int64_t row = (int64_t)w * a.d + j;
-            st<VEC, true>(a.x + row, sx);
-            st<VEC, true>(a.acc + row, sb);
+            const int64_t row = (int64_t)w * a.pitch + j;
+            st<VEC, NT_ST>(a.x + row, sx);
+            st<VEC, NT_ST>(a.acc + row, sb);
         }
         st<VEC, false>(a.snap + j, sb);
     }
 }
 
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
+__global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
+{
+    for_each_tile<VEC>(a.d, a.tiling, [&](int64_t j) { step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY>(a, j); });
+}
+
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
 // shared iterate kept in every worker's row.  Algorithm 2 (Local SGD): y = x - eta G per worker.
 template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
-__global__ __launch_bounds__(BLOCK) void baseline_kernel(const StepArgs a)
+__device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j)
 {
-    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (j >= a.d) return;
     Pack<VEC> av, xs;
     if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
     if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
@@ -232,15 +270,15 @@ __global__ __launch_bounds__(BLOCK) void baseline_kernel(const StepArgs a)
     for (int32_t w0 = 0; w0 < a.W; w0 += WT) {
         Pack<VEC> xv[WT], gv[WT];
 #pragma unroll
-        for (int i = 0; i < WT; ++i) xv[i] = ld<VEC, true>(a.x + (int64_t)(w0 + i) * a.d + j);
+        for (int i = 0; i < WT; ++i) xv[i] = ld<VEC, NT_LD>(a.x + (int64_t)(w0 + i) * a.pitch + j);
         if (w0 == 0) x0 = xv[0];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            gv[i] = gradient<VEC, GS, OS>(a, j, w0 + i, xv[i], av, xs);
+            gv[i] = gradient<VEC, GS, OS>(a, j, (int64_t)(w0 + i) * a.pitch + j, w0 + i, xv[i], av, xs);
             if constexpr (ALGO == ALGO_LOCAL_SGD) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) xv[i].v[e] = fmaf(-a.eta, gv[i].v[e], xv[i].v[e]);
-                if constexpr (!SYNC) st<VEC, true>(a.x + (int64_t)(w0 + i) * a.d + j, xv[i]);
+                if constexpr (!SYNC) st<VEC, NT_ST>(a.x + (int64_t)(w0 + i) * a.pitch + j, xv[i]);
             }
         }
         if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
@@ -263,24 +301,28 @@ __global__ __launch_bounds__(BLOCK) void baseline_kernel(const StepArgs a)
             x0.v[e] = x0.v[e] - (a.eta * g) / sqrtf(b2.v[e] + a.eps2);
         }
         for (int32_t w = 0; w < a.W; ++w) {
-            st<VEC, true>(a.x + (int64_t)w * a.d + j, x0);
-            st<VEC, true>(a.acc + (int64_t)w * a.d + j, b2);
+            st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, x0);
+            st<VEC, NT_ST>(a.acc + (int64_t)w * a.pitch + j, b2);
         }
         st<VEC, false>(a.snap + j, b2);
     } else if constexpr (SYNC) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) sx.v[e] = sx.v[e] / fw;
-        for (int32_t w = 0; w < a.W; ++w) st<VEC, true>(a.x + (int64_t)w * a.d + j, sx);
+        for (int32_t w = 0; w < a.W; ++w) st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, sx);
     }
+}
+
+template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
+__global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
+{
+    for_each_tile<VEC>(a.d, a.tiling, [&](int64_t j) { baseline_body<VEC, WT, GS, OS, ALGO, SYNC>(a, j); });
 }
 
 // Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
 template <int VEC, int WT, bool X_ONLY>
-__global__ __launch_bounds__(BLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
-                                                     float *__restrict__ snap, int64_t d, int32_t W)
+__device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restrict__ acc, float *__restrict__ snap,
+                                          int64_t pitch, int32_t W, const int64_t j)
 {
-    const int64_t j = ((int64_t)blockIdx.x * BLOCK + threadIdx.x) * VEC;
-    if (j >= d) return;
     Pack<VEC> sx, sb;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) sx.v[e] = sb.v[e] = 0.0f;
@@ -288,8 +330,8 @@ __global__ __launch_bounds__(BLOCK) void mean_kernel(float *__restrict__ x, floa
         Pack<VEC> xv[WT], bv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            xv[i] = ld<VEC, true>(x + (int64_t)(w0 + i) * d + j);
-            if constexpr (!X_ONLY) bv[i] = ld<VEC, true>(acc + (int64_t)(w0 + i) * d + j);
+            xv[i] = ld<VEC, NT_LD>(x + (int64_t)(w0 + i) * pitch + j);
+            if constexpr (!X_ONLY) bv[i] = ld<VEC, NT_LD>(acc + (int64_t)(w0 + i) * pitch + j);
         }
         const Pack<VEC> tx = tree_sum<VEC, WT>(xv);
 #pragma unroll
@@ -304,23 +346,31 @@ __global__ __launch_bounds__(BLOCK) void mean_kernel(float *__restrict__ x, floa
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
     for (int32_t w = 0; w < W; ++w) {
-        st<VEC, true>(x + (int64_t)w * d + j, sx);
-        if constexpr (!X_ONLY) st<VEC, true>(acc + (int64_t)w * d + j, sb);
+        st<VEC, NT_ST>(x + (int64_t)w * pitch + j, sx);
+        if constexpr (!X_ONLY) st<VEC, NT_ST>(acc + (int64_t)w * pitch + j, sb);
     }
     if constexpr (!X_ONLY) st<VEC, false>(snap + j, sb);
+}
+
+template <int VEC, int WT, bool X_ONLY>
+__global__ __launch_bounds__(DBLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                     float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W,
+                                                     const Tiling tl)
+{
+    for_each_tile<VEC>(d, tl, [&](int64_t j) { mean_body<VEC, WT, X_ONLY>(x, acc, snap, pitch, W, j); });
 }
 
 // Algorithm 3, Initialize: x[w] = x0 (or 0), acc = snap = b0^2.
 __global__ __launch_bounds__(BLOCK) void init_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                      float *__restrict__ snap, const float *__restrict__ x0,
-                                                     float b0sq, int64_t d, int32_t W)
+                                                     float b0sq, int64_t d, int64_t pitch, int32_t W)
 {
     const int64_t j = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (j >= d) return;
     const float v = x0 ? x0[j] : 0.0f;
     for (int32_t w = 0; w < W; ++w) {
-        x[(int64_t)w * d + j] = v;
-        acc[(int64_t)w * d + j] = b0sq;
+        x[(int64_t)w * pitch + j] = v;
+        acc[(int64_t)w * pitch + j] = b0sq;
     }
     snap[j] = b0sq;
 }
@@ -357,8 +407,8 @@ __global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
     }
     const float *gv = a.vals + pair * a.row_len;
     const int64_t col = (int64_t)r * a.row_len;
-    float *xr = a.x + (int64_t)w * a.d + col;
-    float *br = a.acc + (int64_t)w * a.d + col;
+    float *xr = a.x + (int64_t)w * a.pitch + col;
+    float *br = a.acc + (int64_t)w * a.pitch + col;
     const float *sr = a.snap + col;
     for (int32_t e = lane * 4; e < a.row_len; e += WAVE * 4) {
         const Pack<4> g = ld<4, true>(gv + e);
@@ -453,7 +503,7 @@ __global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__re
 // whose length is read from device memory.
 template <int WT>
 __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
-                                                          float *__restrict__ snap, int64_t d, int32_t W,
+                                                          float *__restrict__ snap, int64_t pitch, int32_t W,
                                                           int32_t row_len, const int32_t *__restrict__ list,
                                                           const uint32_t *__restrict__ count)
 {
@@ -471,8 +521,8 @@ __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x,
                 Pack<4> xv[WT], bv[WT];
 #pragma unroll
                 for (int k = 0; k < WT; ++k) {
-                    xv[k] = ld<4, false>(x + (int64_t)(w0 + k) * d + col + e);
-                    bv[k] = ld<4, false>(acc + (int64_t)(w0 + k) * d + col + e);
+                    xv[k] = ld<4, false>(x + (int64_t)(w0 + k) * pitch + col + e);
+                    bv[k] = ld<4, false>(acc + (int64_t)(w0 + k) * pitch + col + e);
                 }
                 const Pack<4> tx = tree_sum<4, WT>(xv), tb = tree_sum<4, WT>(bv);
 #pragma unroll
@@ -481,8 +531,8 @@ __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x,
 #pragma unroll
             for (int c = 0; c < 4; ++c) { sx.v[c] = sx.v[c] / fw; sb.v[c] = sb.v[c] / fw; }
             for (int32_t w = 0; w < W; ++w) {
-                st<4, false>(x + (int64_t)w * d + col + e, sx);
-                st<4, false>(acc + (int64_t)w * d + col + e, sb);
+                st<4, false>(x + (int64_t)w * pitch + col + e, sx);
+                st<4, false>(acc + (int64_t)w * pitch + col + e, sb);
             }
             st<4, false>(snap + col + e, sb);
         }
@@ -500,6 +550,27 @@ __global__ void philox_debug_kernel(uint32_t c0, uint32_t c1, uint32_t c2, uint3
 
 // ------------------------------------------------------------------------------------------
 // launchers
+// rows of x, acc (and explicit gradients, stored offsets) are pitch >= d elements apart
+static inline bool layout_ok(int64_t d, int64_t pitch, bool vec4)
+{
+    return pitch >= d && (!vec4 || pitch % 4 == 0);
+}
+
+// grid and tiling for n_groups thread-items (one per VEC columns)
+static inline bool tiling_for(int64_t n_groups, int32_t tiles_per_block, int32_t xcds, Tiling *tl, dim3 *grid)
+{
+    if (n_groups <= 0 || tiles_per_block <= 0 || xcds <= 0) return false;
+    const int64_t n_tiles = (n_groups + DBLOCK - 1) / DBLOCK;
+    tl->tiles_per_block = tiles_per_block;
+    tl->xcds = xcds;
+    tl->n_chunks = (n_tiles + tiles_per_block - 1) / tiles_per_block;
+    tl->chunks_per_xcd = (tl->n_chunks + xcds - 1) / xcds;
+    const int64_t nb = tl->chunks_per_xcd * xcds;
+    if (nb > 0x7fffffffLL) return false;
+    *grid = dim3((unsigned)nb);
+    return true;
+}
+
 static inline bool grid_for(int64_t n_threads, dim3 *grid)
 {
     const int64_t nb = (n_threads + BLOCK - 1) / BLOCK;
@@ -513,17 +584,17 @@ static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
 {
     if (a.grad_out) {
         if constexpr (GS == GRAD_EXPLICIT) return hipErrorInvalidValue;
-        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true>), grid, dim3(BLOCK), 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true>), grid, dim3(DBLOCK), 0, s, a);
     } else if (a.algo == ALGO_LOCAL_ADAALTER) {
-        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false>), grid, dim3(BLOCK), 0, s, a);
-        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false>), grid, dim3(BLOCK), 0, s, a);
+        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false>), grid, dim3(DBLOCK), 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false>), grid, dim3(DBLOCK), 0, s, a);
     } else if (a.algo == ALGO_DIST_ADAGRAD) {
-        hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(BLOCK), 0, s, a);
+        hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(DBLOCK), 0, s, a);
     } else {
         if (a.sync)
-            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, true>), grid, dim3(BLOCK), 0, s, a);
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, true>), grid, dim3(DBLOCK), 0, s, a);
         else
-            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, false>), grid, dim3(BLOCK), 0, s, a);
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, false>), grid, dim3(DBLOCK), 0, s, a);
     }
     return hipGetLastError();
 }
@@ -543,12 +614,14 @@ template <int VEC, int WT> static hipError_t launch_step_2(const StepArgs &a, di
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_step(const StepArgs &a, hipStream_t s)
+hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
 {
-    if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0) return hipErrorInvalidValue;
+    StepArgs a = a_in;
+    if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0 || !layout_ok(a.d, a.pitch, a.vec4)) return hipErrorInvalidValue;
     dim3 grid;
     if (a.vec4) {
-        if (a.d % 4 != 0 || !grid_for(a.d / 4, &grid)) return hipErrorInvalidValue;
+        if (a.d % 4 != 0 || !tiling_for(a.d / 4, a.tiling.tiles_per_block, a.tiling.xcds, &a.tiling, &grid))
+            return hipErrorInvalidValue;
         switch (a.wt) {
         case 1: return launch_step_2<4, 1>(a, grid, s);
         case 2: return launch_step_2<4, 2>(a, grid, s);
@@ -557,44 +630,44 @@ hipError_t launch_step(const StepArgs &a, hipStream_t s)
         }
         return hipErrorInvalidValue;
     }
-    if (!grid_for(a.d, &grid)) return hipErrorInvalidValue;
+    if (!tiling_for(a.d, a.tiling.tiles_per_block, a.tiling.xcds, &a.tiling, &grid)) return hipErrorInvalidValue;
     return launch_step_2<1, 1>(a, grid, s);
 }
 
 template <int VEC, int WT>
-static hipError_t launch_mean_2(float *x, float *acc, float *snap, int64_t d, int32_t W, bool x_only, dim3 grid,
-                                hipStream_t s)
+static hipError_t launch_mean_2(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool x_only,
+                                dim3 grid, const Tiling &tl, hipStream_t s)
 {
-    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(BLOCK), 0, s, x, acc, snap, d, W);
-    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(BLOCK), 0, s, x, acc, snap, d, W);
+    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W, tl);
+    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W, tl);
     return hipGetLastError();
 }
 
-hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int32_t W, bool vec4, int32_t wt, bool x_only,
-                       hipStream_t s)
+hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
+                       bool x_only, Tiling tl, hipStream_t s)
 {
-    if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0) return hipErrorInvalidValue;
+    if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0 || !layout_ok(d, pitch, vec4)) return hipErrorInvalidValue;
     dim3 grid;
     if (vec4) {
-        if (d % 4 != 0 || !grid_for(d / 4, &grid)) return hipErrorInvalidValue;
+        if (d % 4 != 0 || !tiling_for(d / 4, tl.tiles_per_block, tl.xcds, &tl, &grid)) return hipErrorInvalidValue;
         switch (wt) {
-        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, W, x_only, grid, s);
-        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, W, x_only, grid, s);
-        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, W, x_only, grid, s);
-        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, W, x_only, grid, s);
+        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
+        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
+        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
+        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
         }
         return hipErrorInvalidValue;
     }
-    if (!grid_for(d, &grid)) return hipErrorInvalidValue;
-    return launch_mean_2<1, 1>(x, acc, snap, d, W, x_only, grid, s);
+    if (!tiling_for(d, tl.tiles_per_block, tl.xcds, &tl, &grid)) return hipErrorInvalidValue;
+    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
 }
 
-hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int32_t W,
-                       hipStream_t s)
+hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
+                       int32_t W, hipStream_t s)
 {
     dim3 grid;
-    if (!grid_for(d, &grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(init_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, x0, b0sq, d, W);
+    if (!grid_for(d, &grid) || !layout_ok(d, pitch, false)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(init_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, x0, b0sq, d, pitch, W);
     return hipGetLastError();
 }
 
@@ -621,7 +694,8 @@ hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s)
 {
     const int64_t pairs = (int64_t)a.W * a.k;
     if (pairs == 0) return hipSuccess;
-    if (a.row_len <= 0 || a.row_len % 4 != 0 || a.n_rows * a.row_len != a.d) return hipErrorInvalidValue;
+    if (a.row_len <= 0 || a.row_len % 4 != 0 || a.n_rows * a.row_len != a.d || a.pitch < a.d || a.pitch % 4 != 0)
+        return hipErrorInvalidValue;
     const int64_t nb = (pairs + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (nb > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(sparse_step_kernel, dim3((unsigned)nb), dim3(BLOCK), 0, s, a);
@@ -640,14 +714,14 @@ hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *
     return hipGetLastError();
 }
 
-hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t d, int32_t W, int32_t row_len,
+hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t row_len,
                             const int32_t *list, const uint32_t *count, hipStream_t s)
 {
     const dim3 grid(2048), block(BLOCK);
-    if (W % 8 == 0) hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
-    else if (W % 4 == 0) hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
-    else if (W % 2 == 0) hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
-    else hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, d, W, row_len, list, count);
+    if (W % 8 == 0) hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
+    else if (W % 4 == 0) hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
+    else if (W % 2 == 0) hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
+    else hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
     return hipGetLastError();
 }
 

@@ -98,6 +98,56 @@ def test_unaligned_buffers_take_scalar_path(B):
     parity.assert_state(host(x), host(acc), host(snap), o, parity.FULL_RUN, what="unaligned", scale=sc)
 
 
+@pytest.mark.parametrize("W,d,pitch", [(8, D_SMALL, D_SMALL + 64), (4, 4 * 300, 4 * 300 + 8), (3, 1001, 1003), (2, 4096, 4096 + 1024)])
+def test_pitched_rows(B, W, d, pitch):
+    """Rows `pitch` elements apart (dense, generator with stored offsets, fused sync, sparse): same results."""
+    import torch
+    H = 3
+    rng = np.random.default_rng(17)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    p = pitch
+    xbuf = torch.full((W, p), 7.0, device="cuda:0"); accbuf = torch.full((W, p), 7.0, device="cuda:0")
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0, x=xbuf[:, :d], acc=accbuf[:, :d], pitch=p); g.init_state(dev(x0))
+    assert g.pitch >= d and g.x.stride(0) == g.pitch
+    sc = parity.Scale(o)
+    for t in range(1, 2 * H + 1):                      # explicit gradients, fused sync
+        G = rng.standard_normal((W, d)).astype(np.float32)
+        o.local_step_dense(G); sc.update(o)
+        if t % H == 0:
+            o.sync()
+        g.step_dense(g.rows(dev(G)))
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="pitched dense", scale=sc)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    off = (0.1 * rng.standard_normal((W, d))).astype(np.float32)
+    o.set_generator(oracle.GEN_QUADRATIC, 5, a, xs, off, oracle.OFF_ARRAY, 0.1, 0.1)
+    g.set_generator(B.GEN_QUADRATIC, 5, dev(a), dev(xs), g.rows(dev(off)), B.OFF_ARRAY, 0.1, 0.1)
+    for t in range(H + 1):                             # generator with stored offsets, separate sync
+        G_ref = o.gradient(o.t + 1)
+        G_gpu = host(g.generate_gradient())
+        assert np.max(np.abs(G_gpu - G_ref) / _gen_scale(a, o.x, xs, 0.1, 0.1)) <= 1e-6
+        o.local_step_gen(); g.local_step_gen()
+        if o.steps_since_sync == H:
+            o.sync(); g.sync()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="pitched generator")
+    if d % 16 == 0 and g.pitch % 4 == 0:               # sparse rows of 16
+        o.sync(); g.sync()
+        rows = d // 16
+        sc = parity.Scale(o)
+        for t in range(H):
+            idx = np.stack([rng.permutation(rows)[:min(rows, 20)] for _ in range(W)]).astype(np.int32)
+            vals = rng.standard_normal((W, idx.shape[1], 16)).astype(np.float32)
+            o.local_step_sparse(idx, vals, 16); g.local_step_sparse(dev(idx), dev(vals), 16); sc.update(o)
+        assert np.array_equal(g.dirty_rows(), o.dirty_rows())
+        o.sync(); g.sync()
+        parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="pitched sparse", scale=sc)
+    # the padding between rows is never written, and arrays with another pitch are refused
+    if g.pitch != d:
+        assert bool((xbuf[:, d:] == 7.0).all()) and bool((accbuf[:, d:] == 7.0).all())
+        with pytest.raises(ValueError):
+            g.step_dense(dev(np.zeros((W, d), np.float32)))
+
+
 def test_fused_step_equals_local_step_plus_sync(B):
     import torch
     W, H, d = 8, 3, D_SMALL
@@ -371,7 +421,7 @@ def test_config3_explicit_gradient_pool(B):
     g.set_generator(B.GEN_NOISE, c.seed, dev(sig))
     o = Oracle(len(cols), c.W, H, c.eta, c.eps); o.set_columns(cols); o.init_state()
     o.set_generator(oracle.GEN_NOISE, c.seed, sig[cols])
-    pool = torch.empty((c.W, c.d), dtype=torch.float32, device="cuda:0")
+    pool = g.rows()
     sc = parity.Scale(o)
     for t in range(1, 2 * H + 1):
         g.generate_gradient(pool)                       # materialise this iteration's gradient, then stream it
