@@ -72,3 +72,39 @@ def test_create_rejects_bad_arguments():
                  (4, 1, 1, 0.5, -1.0)]:
         with pytest.raises(ValueError):
             oracle.Oracle(*args)
+
+
+def test_tolerance_calibration_fp32_statements_meet_the_gpu_bars():
+    """The same statements evaluated in fp32 (the oracle's fp32 build) stay within the bars the GPU tests use,
+    i.e. the bars are what fp32 arithmetic can deliver and no looser."""
+    import parity
+    from paper_1911_09030_amd import workloads as wl
+    # explicit gradients: identical inputs on both sides
+    W, H, d, T = 4, 4, 4096, 32
+    rng = np.random.default_rng(3)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    sig = np.power(10.0, rng.uniform(-3, 1, d)).astype(np.float32)
+    o64 = oracle.Oracle(d, W, H, 0.5, 1.0); o64.init_state(x0)
+    o32 = oracle.Oracle(d, W, H, 0.5, 1.0, precision="f32"); o32.init_state(x0)
+    sc = parity.Scale(o64)
+    for t in range(1, T + 1):
+        G = rng.standard_normal((W, d)).astype(np.float32) * sig[None, :]
+        o64.local_step_dense(G); o32.local_step_dense(G); sc.update(o64)
+        if t == 1:
+            parity.assert_state(o32.x, o32.acc, o32.snap, o64, parity.ONE_STEP, what="fp32 one step", scale=sc)
+        if t % H == 0:
+            o64.sync(); o32.sync()
+    parity.assert_state(o32.x, o32.acc, o32.snap, o64, parity.FULL_RUN, what="fp32 full run", scale=sc)
+    # generator-fed, the small configuration on a column sample, full length
+    c = wl.WORKLOADS["c1"]
+    cols = wl.column_sample(c.d, 512, seed=1)
+    a = wl.curvature(c.d, c.seed, c.a_dist)[cols]; xs = wl.optimum(c.d, c.seed)[cols]
+    runs = []
+    for prec in ("f64", "f32"):
+        o = oracle.Oracle(len(cols), c.W, c.H, c.eta, c.eps, precision=prec)
+        o.set_columns(cols); o.init_state()
+        o.set_generator(oracle.GEN_QUADRATIC, c.seed, a, xs, None, oracle.OFF_PHILOX, c.noise_scale, c.off_scale)
+        for _ in range(c.T):
+            o.step_gen()
+        runs.append(o)
+    parity.assert_state(runs[1].x, runs[1].acc, runs[1].snap, runs[0], 1e-5, floor_x=1.0, what="fp32 generator run")
