@@ -83,9 +83,13 @@ int laa_set_warmup(laa_handle h, int64_t warmup_steps);
  * laa_step_dense / laa_step_gen only.  Only before the first step. */
 int laa_set_algorithm(laa_handle h, int32_t algo);
 
-/* Tuning knob: how many workers' rows a thread loads before it starts computing (1, 2, 4 or 8,
- * must divide W; default: the largest of those that divides W).  Results do not depend on it
- * except through the order of the worker-axis sum when W exceeds it. */
+/* Tuning knob for the dense kernels.  1, 2, 4 or 8 (must divide W; default: the largest that
+ * does): a thread handles all W workers of its column group and loads that many workers' rows
+ * before it starts computing.  0: in steps that do not average, every thread block handles ONE
+ * worker of a 256-column tile instead (two read-modify-write streams per thread; the W blocks of
+ * a tile run on the same XCD so that snap, a, xstar are re-read from its L2, not from HBM);
+ * steps that average still use the default batch.  Results do not depend on the choice except
+ * through the order of the worker-axis sum when W exceeds the batch. */
 int laa_set_tile(laa_handle h, int32_t workers_per_batch);
 
 /* Hand over the state arrays (device, caller-owned, must outlive the handle's

@@ -20,7 +20,7 @@ struct laa_ctx {
     hipStream_t stream = nullptr;
     bool attached = false, vec4 = false, gen_aligned16 = true;
     int32_t wt = 1;
-    laa::Tiling tiling;
+    bool split = false;     // one worker per thread block in non-sync steps (laa_set_tile(h, 0))
     int64_t t = 0;          // iterations done
     int32_t s = 0;          // local steps since the last sync (t' - 1 before a step)
     // generator
@@ -157,7 +157,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
     a.algo = h->algo;
     a.wt = h->wt;
-    a.tiling = h->tiling;
+    a.split = h->split;
     a.vec4 = h->vec4 && (kind == STEP_DENSE ? aligned(grads, 16) : h->gen_aligned16);
     if (!a.vec4) a.wt = 1;
 
@@ -243,9 +243,15 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch)
 {
     if (!h) return fail(LAA_EINVAL, "null handle");
     const int32_t wt = workers_per_batch;
+    if (wt == 0) {              // one worker per thread block in non-sync steps
+        h->split = true;
+        h->wt = pick_wt(h->W);
+        return LAA_OK;
+    }
     if (!(wt == 1 || wt == 2 || wt == 4 || wt == 8) || h->W % wt != 0)
-        return fail(LAA_EINVAL, "workers_per_batch must be 1, 2, 4 or 8 and divide W");
+        return fail(LAA_EINVAL, "workers_per_batch must be 0, or 1, 2, 4 or 8 and divide W");
     h->wt = wt;
+    h->split = false;
     return LAA_OK;
 }
 
@@ -324,7 +330,6 @@ int laa_generate_gradient(laa_handle h, float *out)
     a.grad_source = h->gen_mode; a.off_source = h->off_mode;
     a.vec4 = h->vec4 && h->gen_aligned16 && aligned(out, 16);
     a.wt = a.vec4 ? h->wt : 1;
-    a.tiling = h->tiling;
     hipError_t e = laa::launch_step(a, h->stream);
     return e == hipSuccess ? LAA_OK : hip_fail(e, "gradient kernel launch");
 }
@@ -374,7 +379,7 @@ int laa_sync(laa_handle h)
         e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
-        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->tiling, h->stream);
+        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->stream);
         if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
         h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
     }

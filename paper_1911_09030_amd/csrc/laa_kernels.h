@@ -10,15 +10,6 @@ enum GradSource { GRAD_EXPLICIT = 0, GRAD_QUADRATIC = 1, GRAD_NOISE = 2 };
 enum OffsetSource { OFFSET_NONE = 0, OFFSET_ARRAY = 1, OFFSET_PHILOX = 2 };
 enum Algo { ALGO_LOCAL_ADAALTER = 0, ALGO_DIST_ADAGRAD = 1, ALGO_LOCAL_SGD = 2 };
 
-// How thread blocks are mapped to columns: each block walks tiles_per_block consecutive tiles, and blocks are
-// dealt so that each of `xcds` dies owns one contiguous range.  n_chunks / chunks_per_xcd are filled by the launcher.
-struct Tiling {
-    int32_t tiles_per_block = 1;
-    int32_t xcds = 1;
-    int64_t n_chunks = 0;
-    int64_t chunks_per_xcd = 0;
-};
-
 struct StepArgs {
     float *x;            // [W][pitch], d used
     float *acc;          // [W][pitch]
@@ -41,13 +32,13 @@ struct StepArgs {
     bool sync;           // average over the worker axis in the same pass
     bool vec4;           // pointers 16-byte aligned and d % 4 == 0
     int32_t wt;          // workers loaded per batch (1, 2, 4 or 8; must divide W)
-    Tiling tiling;
+    bool split;          // non-sync steps: one worker per thread block instead of all W (see block_work)
     int32_t algo;
 };
 
 hipError_t launch_step(const StepArgs &a, hipStream_t s);
 hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
-                       bool x_only, Tiling tl, hipStream_t s);
+                       bool x_only, hipStream_t s);
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
                        int32_t W, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);

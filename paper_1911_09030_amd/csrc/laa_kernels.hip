@@ -62,21 +62,30 @@ template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const P
 }
 
 // ------------------------------------------------------------------------------------------
-// Thread block -> columns.  A tile is DBLOCK * VEC consecutive columns (one group per thread).  A thread block
-// walks a chunk of tiles_per_block consecutive tiles, and chunks are dealt so that the thread blocks that land
-// on the same XCD (the hardware deals consecutive block ids round-robin over the XCDs) own one contiguous range
-// of columns: each XCD then streams through its own slice of every array, which keeps the pages and cache lines
-// it touches at any moment few and dense.
-template <int VEC, typename F> __device__ __forceinline__ void for_each_tile(int64_t d, const Tiling &tl, F body)
+// Thread block -> work.  A tile is DBLOCK * VEC consecutive columns (one group per thread).
+//   joint: block b owns tile b for all W workers (needed when the step also averages over the workers).
+//   split: block b owns ONE worker of a tile, so a thread has two read-modify-write streams instead of 2W.
+//          The W blocks of a tile re-read snap, a, xstar; they are given block ids 8 apart, which the
+//          hardware's round-robin deal of consecutive block ids over the 8 XCDs puts on the same XCD close
+//          in time, so those re-reads hit that XCD's L2 and HBM traffic stays at the algorithmic bytes:
+//              b -> lo = b mod 8, w = (b div 8) mod W, hi = b div 8W, tile = 8 hi + lo.
+template <int VEC, bool SPLIT>
+__device__ __forceinline__ bool block_work(int64_t d, int32_t W, int64_t *j, int32_t *w_begin, int32_t *w_end)
 {
-    int64_t chunk = blockIdx.x;
-    if (tl.xcds > 1) {
-        const int64_t x = chunk % tl.xcds, i = chunk / tl.xcds;
-        chunk = x * tl.chunks_per_xcd + i;
-        if (chunk >= tl.n_chunks) return;
+    int64_t tile;
+    if constexpr (SPLIT) {
+        const int64_t b = blockIdx.x, n_tiles = (d / VEC + DBLOCK - 1) / DBLOCK;
+        tile = (b / (8 * (int64_t)W)) * 8 + (b & 7);
+        *w_begin = (int32_t)((b >> 3) % W);
+        *w_end = *w_begin + 1;
+        if (tile >= n_tiles) return false;
+    } else {
+        tile = blockIdx.x;
+        *w_begin = 0;
+        *w_end = W;
     }
-    int64_t j = (chunk * tl.tiles_per_block * DBLOCK + threadIdx.x) * VEC;
-    for (int32_t it = 0; it < tl.tiles_per_block && j < d; ++it, j += DBLOCK * VEC) body(j);
+    *j = (tile * DBLOCK + threadIdx.x) * VEC;
+    return *j < d;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -188,9 +197,9 @@ template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const P
 //   SYNC: x, B2 <- mean over workers of y, A2; B2_sync <- that mean      (Synchronize branch)
 //   GRAD_ONLY: write g and change nothing (used to materialise gradients)
 template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
-__device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j)
+__device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, const int32_t w_begin,
+                                          const int32_t w_end)
 {
-
     Pack<VEC> av, xs, step;
     if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
     if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
@@ -204,7 +213,7 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) sx.v[e] = sb.v[e] = 0.0f;
 
-    for (int32_t w0 = 0; w0 < a.W; w0 += WT) {
+    for (int32_t w0 = w_begin; w0 < w_end; w0 += WT) {
         Pack<VEC> xv[WT], bv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
@@ -249,10 +258,14 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j)
     }
 }
 
-template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT>
 __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
 {
-    for_each_tile<VEC>(a.d, a.tiling, [&](int64_t j) { step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY>(a, j); });
+    static_assert(!SPLIT || (WT == 1 && !SYNC), "a split block owns one worker and cannot average");
+    int64_t j;
+    int32_t w_begin, w_end;
+    if (block_work<VEC, SPLIT>(a.d, a.W, &j, &w_begin, &w_end))
+        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY>(a, j, w_begin, w_end);
 }
 
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
@@ -315,7 +328,9 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
 template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
 __global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
 {
-    for_each_tile<VEC>(a.d, a.tiling, [&](int64_t j) { baseline_body<VEC, WT, GS, OS, ALGO, SYNC>(a, j); });
+    int64_t j;
+    int32_t w_begin, w_end;
+    if (block_work<VEC, false>(a.d, a.W, &j, &w_begin, &w_end)) baseline_body<VEC, WT, GS, OS, ALGO, SYNC>(a, j);
 }
 
 // Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
@@ -354,10 +369,11 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
 
 template <int VEC, int WT, bool X_ONLY>
 __global__ __launch_bounds__(DBLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
-                                                     float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W,
-                                                     const Tiling tl)
+                                                     float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W)
 {
-    for_each_tile<VEC>(d, tl, [&](int64_t j) { mean_body<VEC, WT, X_ONLY>(x, acc, snap, pitch, W, j); });
+    int64_t j;
+    int32_t w_begin, w_end;
+    if (block_work<VEC, false>(d, W, &j, &w_begin, &w_end)) mean_body<VEC, WT, X_ONLY>(x, acc, snap, pitch, W, j);
 }
 
 // Algorithm 3, Initialize: x[w] = x0 (or 0), acc = snap = b0^2.
@@ -556,16 +572,12 @@ static inline bool layout_ok(int64_t d, int64_t pitch, bool vec4)
     return pitch >= d && (!vec4 || pitch % 4 == 0);
 }
 
-// grid and tiling for n_groups thread-items (one per VEC columns)
-static inline bool tiling_for(int64_t n_groups, int32_t tiles_per_block, int32_t xcds, Tiling *tl, dim3 *grid)
+// grid of the dense kernels for n_groups thread-items (one per VEC columns); split: one block per (tile, worker)
+static inline bool dense_grid(int64_t n_groups, bool split, int32_t W, dim3 *grid)
 {
-    if (n_groups <= 0 || tiles_per_block <= 0 || xcds <= 0) return false;
+    if (n_groups <= 0) return false;
     const int64_t n_tiles = (n_groups + DBLOCK - 1) / DBLOCK;
-    tl->tiles_per_block = tiles_per_block;
-    tl->xcds = xcds;
-    tl->n_chunks = (n_tiles + tiles_per_block - 1) / tiles_per_block;
-    tl->chunks_per_xcd = (tl->n_chunks + xcds - 1) / xcds;
-    const int64_t nb = tl->chunks_per_xcd * xcds;
+    const int64_t nb = split ? (n_tiles + 7) / 8 * 8 * (int64_t)W : n_tiles;
     if (nb > 0x7fffffffLL) return false;
     *grid = dim3((unsigned)nb);
     return true;
@@ -584,10 +596,13 @@ static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
 {
     if (a.grad_out) {
         if constexpr (GS == GRAD_EXPLICIT) return hipErrorInvalidValue;
-        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true>), grid, dim3(DBLOCK), 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true, false>), grid, dim3(DBLOCK), 0, s, a);
     } else if (a.algo == ALGO_LOCAL_ADAALTER) {
-        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false>), grid, dim3(DBLOCK), 0, s, a);
-        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false>), grid, dim3(DBLOCK), 0, s, a);
+        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false, false>), grid, dim3(DBLOCK), 0, s, a);
+        else if (a.split) {
+            if constexpr (WT == 1) hipLaunchKernelGGL((step_kernel<VEC, 1, GS, OS, false, false, true>), grid, dim3(DBLOCK), 0, s, a);
+            else return hipErrorInvalidValue;
+        } else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false, false>), grid, dim3(DBLOCK), 0, s, a);
     } else if (a.algo == ALGO_DIST_ADAGRAD) {
         hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(DBLOCK), 0, s, a);
     } else {
@@ -618,10 +633,12 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
 {
     StepArgs a = a_in;
     if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0 || !layout_ok(a.d, a.pitch, a.vec4)) return hipErrorInvalidValue;
+    // one worker per block only for the plain Local AdaAlter step (no averaging in the same pass)
+    a.split = a.split && a.vec4 && !a.sync && !a.grad_out && a.algo == ALGO_LOCAL_ADAALTER && a.W > 1;
+    if (a.split) a.wt = 1;
     dim3 grid;
     if (a.vec4) {
-        if (a.d % 4 != 0 || !tiling_for(a.d / 4, a.tiling.tiles_per_block, a.tiling.xcds, &a.tiling, &grid))
-            return hipErrorInvalidValue;
+        if (a.d % 4 != 0 || !dense_grid(a.d / 4, a.split, a.W, &grid)) return hipErrorInvalidValue;
         switch (a.wt) {
         case 1: return launch_step_2<4, 1>(a, grid, s);
         case 2: return launch_step_2<4, 2>(a, grid, s);
@@ -630,36 +647,36 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
         }
         return hipErrorInvalidValue;
     }
-    if (!tiling_for(a.d, a.tiling.tiles_per_block, a.tiling.xcds, &a.tiling, &grid)) return hipErrorInvalidValue;
+    if (!dense_grid(a.d, false, a.W, &grid)) return hipErrorInvalidValue;
     return launch_step_2<1, 1>(a, grid, s);
 }
 
 template <int VEC, int WT>
 static hipError_t launch_mean_2(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool x_only,
-                                dim3 grid, const Tiling &tl, hipStream_t s)
+                                dim3 grid, hipStream_t s)
 {
-    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W, tl);
-    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W, tl);
+    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
+    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
     return hipGetLastError();
 }
 
 hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
-                       bool x_only, Tiling tl, hipStream_t s)
+                       bool x_only, hipStream_t s)
 {
     if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0 || !layout_ok(d, pitch, vec4)) return hipErrorInvalidValue;
     dim3 grid;
     if (vec4) {
-        if (d % 4 != 0 || !tiling_for(d / 4, tl.tiles_per_block, tl.xcds, &tl, &grid)) return hipErrorInvalidValue;
+        if (d % 4 != 0 || !dense_grid(d / 4, false, W, &grid)) return hipErrorInvalidValue;
         switch (wt) {
-        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
-        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
-        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
-        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
+        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, pitch, W, x_only, grid, s);
+        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, pitch, W, x_only, grid, s);
+        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, pitch, W, x_only, grid, s);
+        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, pitch, W, x_only, grid, s);
         }
         return hipErrorInvalidValue;
     }
-    if (!tiling_for(d, tl.tiles_per_block, tl.xcds, &tl, &grid)) return hipErrorInvalidValue;
-    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, grid, tl, s);
+    if (!dense_grid(d, false, W, &grid)) return hipErrorInvalidValue;
+    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, grid, s);
 }
 
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,

@@ -154,14 +154,26 @@ def test_fused_step_equals_local_step_plus_sync(B):
     rng = np.random.default_rng(6)
     a = B.LocalAdaAlter(d, W, H, 0.5, 1.0); a.init_state()
     b = B.LocalAdaAlter(d, W, H, 0.5, 1.0); b.init_state()
+    # the same with every thread-to-worker mapping: all W workers per thread in batches of 8, 4, 1, and one
+    # worker per thread block (0)
+    others = []
+    for tile in (8, 0, 4, 1):
+        c = B.LocalAdaAlter(d, W, H, 0.5, 1.0); c.init_state(); c.set_tile(tile)
+        others.append(c)
     for t in range(1, 3 * H + 1):
         G = dev(rng.standard_normal((W, d)).astype(np.float32))
         a.step_dense(G)
         b.local_step_dense(G)
+        for c in others:
+            c.step_dense(G)
         if t % H == 0:
             b.sync()
         assert a.counters() == b.counters()
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        for c in others[:2]:       # batch of 8 / one worker per block: the same arithmetic as the default
+            assert torch.equal(a.x, c.x) and torch.equal(a.acc, c.acc), f"mapping differs at t={t}"
+        for c in others[2:]:
+            assert torch.allclose(a.x, c.x, rtol=1e-5, atol=1e-5) and torch.allclose(a.acc, c.acc, rtol=1e-5)
     assert torch.equal(a.x, b.x) and torch.equal(a.acc, b.acc) and torch.equal(a.snap, b.snap)
 
 
@@ -193,12 +205,15 @@ def _gen_scale(a, x, xs, off_scale, noise_scale):
     return np.abs(a)[None, :] * (np.abs(x) + np.abs(xs)[None, :] + 4 * off_scale) + 5 * noise_scale
 
 
-@pytest.mark.parametrize("mode,off_mode,W,d", [("quad", "none", 4, D_SMALL), ("quad", "array", 4, D_SMALL),
-                                               ("quad", "philox", 8, D_SMALL), ("quad", "philox", 3, 4 * 300 + 2),
-                                               ("noise", "none", 8, D_SMALL), ("noise", "none", 2, 999)])
-def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d):
+@pytest.mark.parametrize("mode,off_mode,W,d,tile", [("quad", "none", 4, D_SMALL, None), ("quad", "array", 4, D_SMALL, None),
+                                                    ("quad", "philox", 8, D_SMALL, None),
+                                                    ("quad", "philox", 3, 4 * 300 + 2, None),
+                                                    ("noise", "none", 8, D_SMALL, None), ("noise", "none", 2, 999, None),
+                                                    ("quad", "philox", 8, D_SMALL, 0), ("quad", "array", 5, 4 * 701, 0),
+                                                    ("noise", "none", 3, 4 * 64 * 9, 0), ("quad", "philox", 16, 4 * 333, 4)])
+def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d, tile):
     import torch
-    say(f"generator mode={mode} off={off_mode} W={W} d={d}")
+    say(f"generator mode={mode} off={off_mode} W={W} d={d} tile={tile}")
     H, seed = 4, 1234567890123
     rng = np.random.default_rng(7)
     a = rng.uniform(0.1, 10, d).astype(np.float32)
@@ -212,6 +227,10 @@ def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d):
     g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(dev(x0))
     u = B.LocalAdaAlter(d, W, H, 0.5, 1.0); u.init_state(dev(x0))       # unfused twin: generate, then explicit step
     da, dxs, doff = dev(a), dev(xs), dev(off)
+    if tile is not None:
+        g.set_tile(tile)
+        if tile:
+            u.set_tile(tile)         # same batches, hence the same order of the worker-axis sum
     for inst in (g, u):
         inst.set_generator(gm, seed, da, dxs if mode == "quad" else None, doff if off_mode == "array" else None,
                            om, 0.1, 0.1)
