@@ -37,6 +37,8 @@ def parse():
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
     p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
+    p.add_argument("--no-lazy-replicas", action="store_true",
+                   help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--calibrate-copy", type=int, default=0,
                    help="after the run, launch the plain copy kernel this many times over one row of d floats "
@@ -170,6 +172,9 @@ def main():
         updates_per_step = W * c.k * c.row_len + W * dd
     if args.tile:
         g.set_tile(args.tile)
+    lazy = not args.no_lazy_replicas and c.kind != "embedding"
+    if lazy:
+        g.set_lazy_replicas(True)
 
     # warm-up (untimed), then realign to a period boundary so the timed region holds K/H syncs
     t = 0
@@ -198,14 +203,17 @@ def main():
     per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
     if c.kind == "embedding":                 # the roofline line is the row-sparse step alone
         per_step_ms = [ev[i].elapsed_time(mid[t_first + i]) for i in range(K)]
-    # the dominant kernel is the non-sync step; sync iterations are the ones with (i+1) % H == 0
-    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0] or per_step_ms
+    # the dominant kernel is the plain step: not the averaging one ((i+1) % H == 0) and, with lazy replicas, not the
+    # one right after it (i % H == 0), which reads the collapsed state
+    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not (lazy and i % H == 0)] or per_step_ms
+    post_sync = [per_step_ms[i] for i in range(K) if lazy and i % H == 0 and (i + 1) % H != 0]
     sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
     kern_ms = sum(plain) / len(plain)
     achieved = step_bytes / (kern_ms * 1e-3) / 1e9
     value = updates_per_step * K / wall
 
-    assert bool(torch.isfinite(g.x[0, :4096]).all()), "non-finite parameters after the run"
+    g.materialize()
+    assert bool(torch.isfinite(g.x[W - 1, :4096]).all()), "non-finite parameters after the run"
     for _ in range(args.calibrate_copy):          # reads 4d bytes, writes 4d bytes
         B.debug_copy(g.acc[0], g.x[0])
     torch.cuda.synchronize()
@@ -218,9 +226,10 @@ def main():
         "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
-                               f"row_pitch={g.pitch}",
+                               f"lazy_replicas={'on' if lazy else 'off'} row_pitch={g.pitch}",
                    "syncs_in_timed_region": len(sync_it),
                    "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
+                   "ms_post_sync_iteration": (sum(post_sync) / len(post_sync)) if post_sync else None,
                    "method_bytes_per_element_update": 16 + 4 / W + (16 * W + 4) / (W * H)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(kernel_tag),

@@ -92,6 +92,17 @@ int laa_set_algorithm(laa_handle h, int32_t algo);
  * through the order of the worker-axis sum when W exceeds the batch. */
 int laa_set_tile(laa_handle h, int32_t workers_per_batch);
 
+/* Lazy replicas (off by default).  Right after a Synchronize every worker holds the same x and
+ * the same B2 (= snap), so with this option a step or laa_sync that averages writes that common
+ * state once (row 0 of x, and snap) instead of into all W rows, and the next step reads it from
+ * there for every worker: per column one sync period moves 2W floats less on the averaging pass
+ * and 2(W-1) floats less on the pass after it.  While the state is collapsed, rows 1..W-1 of x
+ * and all rows of acc are stale; call laa_materialize before reading them (the library does so
+ * itself before a sparse step, an Algorithm 1/2 step, or when the option is switched off).
+ * Results are bit-identical to the default. */
+int laa_set_lazy_replicas(laa_handle h, int32_t on);
+int laa_materialize(laa_handle h);
+
 /* Hand over the state arrays (device, caller-owned, must outlive the handle's
  * use): x [W][d], acc [W][d] (running B2 of each worker), snap [d] (B2 at the
  * last sync), and the HIP stream (hipStream_t, may be null for the default

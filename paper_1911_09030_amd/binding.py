@@ -21,7 +21,7 @@ ALGO_LOCAL_ADAALTER, ALGO_DIST_ADAGRAD, ALGO_LOCAL_SGD = 0, 1, 2
 
 EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
-    "laa_set_tile", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
+    "laa_set_tile", "laa_set_lazy_replicas", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_get_dirty_rows", "laa_bytes_moved",
     "laa_debug_philox", "laa_debug_copy",
@@ -55,6 +55,8 @@ def lib():
         "laa_set_warmup": [vp, i64],
         "laa_set_algorithm": [vp, i32],
         "laa_set_tile": [vp, i32],
+        "laa_set_lazy_replicas": [vp, i32],
+        "laa_materialize": [vp],
         "laa_attach": [vp, vp, vp, vp, vp],
         "laa_attach_pitched": [vp, vp, vp, vp, i64, vp],
         "laa_init_state": [vp, vp],
@@ -162,6 +164,12 @@ class LocalAdaAlter:
 
     def set_tile(self, workers_per_batch):
         _check(self.L.laa_set_tile(self.h, int(workers_per_batch)))
+
+    def set_lazy_replicas(self, on=True):
+        _check(self.L.laa_set_lazy_replicas(self.h, 1 if on else 0))
+
+    def materialize(self):
+        _check(self.L.laa_materialize(self.h))
 
     def init_state(self, x0=None):
         _check(self.L.laa_init_state(self.h, _dev_ptr(x0, self.torch.float32)))

@@ -21,6 +21,8 @@ struct laa_ctx {
     bool attached = false, vec4 = false, gen_aligned16 = true;
     int32_t wt = 1;
     bool split = false;     // one worker per thread block in non-sync steps (laa_set_tile(h, 0))
+    bool lazy = false;      // keep the post-sync state once (row 0 of x, snap) until the next step
+    bool collapsed = false; // rows 1.. of x and all of acc are stale; row 0 of x and snap hold the common state
     int64_t t = 0;          // iterations done
     int32_t s = 0;          // local steps since the last sync (t' - 1 before a step)
     // generator
@@ -113,6 +115,16 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     return LAA_OK;
 }
 
+// Expand the collapsed post-sync state into every worker's row.
+int materialize(laa_ctx *h)
+{
+    if (!h->collapsed) return LAA_OK;
+    hipError_t e = laa::launch_materialize(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "materialize kernel launch");
+    h->collapsed = false;
+    return LAA_OK;
+}
+
 int clear_dirty(laa_ctx *h)
 {
     if (!h->dirty) return LAA_OK;
@@ -138,6 +150,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
         return fail(LAA_EMODE, "this update rule runs through laa_step_* only");
     if (!adagrad && h->s >= h->H)
         return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
+    if (h->algo != LAA_ALGO_LOCAL_ADAALTER && (rc = materialize(h)) != LAA_OK) return rc;
 
     laa::StepArgs a{};
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
@@ -155,6 +168,8 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.grad_source = kind == STEP_DENSE ? laa::GRAD_EXPLICIT : h->gen_mode;
     a.off_source = kind == STEP_DENSE ? laa::OFFSET_NONE : h->off_mode;
     a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
+    a.collapsed_in = h->collapsed;
+    a.collapsed_out = a.sync && h->lazy && h->algo == LAA_ALGO_LOCAL_ADAALTER;
     a.algo = h->algo;
     a.wt = h->wt;
     a.split = h->split;
@@ -172,6 +187,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     h->t += 1;
     h->s += 1;
     h->sparse_only_since_sync = false;
+    h->collapsed = a.collapsed_out;
     if (a.sync) {
         h->bytes += (16 * W + 4) * d;                       // literal sync traffic: read 2W, write 2W+1 floats
         h->s = 0;
@@ -255,6 +271,24 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch)
     return LAA_OK;
 }
 
+int laa_set_lazy_replicas(laa_handle h, int32_t on)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (!on && h->collapsed) {
+        int rc = check_ready(h);
+        if (rc == LAA_OK) rc = materialize(h);
+        if (rc != LAA_OK) return rc;
+    }
+    h->lazy = on != 0;
+    return LAA_OK;
+}
+
+int laa_materialize(laa_handle h)
+{
+    int rc = check_ready(h);
+    return rc != LAA_OK ? rc : materialize(h);
+}
+
 int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream)
 {
     return laa_attach_pitched(h, x, acc, snap, h ? h->d : 0, hip_stream);
@@ -283,7 +317,7 @@ int laa_init_state(laa_handle h, const float *x0)
     const float b0sq = (float)(h->b0 * h->b0);
     hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "init kernel launch");
-    h->t = 0; h->s = 0; h->bytes = 0; h->sparse_only_since_sync = true;
+    h->t = 0; h->s = 0; h->bytes = 0; h->sparse_only_since_sync = true; h->collapsed = false;
     return clear_dirty(h);
 }
 
@@ -328,6 +362,7 @@ int laa_generate_gradient(laa_handle h, float *out)
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.t_lo = (uint32_t)(h->t + 1);
     a.grad_source = h->gen_mode; a.off_source = h->off_mode;
+    a.collapsed_in = h->collapsed;
     a.vec4 = h->vec4 && h->gen_aligned16 && aligned(out, 16);
     a.wt = a.vec4 ? h->wt : 1;
     hipError_t e = laa::launch_step(a, h->stream);
@@ -351,6 +386,7 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
         return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
     rc = ensure_sparse(h, row_len);
     if (rc != LAA_OK) return rc;
+    if ((rc = materialize(h)) != LAA_OK) return rc;      // the row kernel reads every worker's own rows
     laa::SparseArgs a{};
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
     a.idx = idx; a.vals = vals; a.dirty = h->dirty; a.bad = h->bad;
@@ -379,9 +415,12 @@ int laa_sync(laa_handle h)
         e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
-        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only, h->stream);
+        const bool collapse = h->lazy && !x_only;
+        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only,
+                             collapse, h->stream);
         if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
         h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
+        h->collapsed = collapse;
     }
     h->s = 0;
     h->sparse_only_since_sync = true;

@@ -33,12 +33,16 @@ struct StepArgs {
     bool vec4;           // pointers 16-byte aligned and d % 4 == 0
     int32_t wt;          // workers loaded per batch (1, 2, 4 or 8; must divide W)
     bool split;          // non-sync steps: one worker per thread block instead of all W (see block_work)
+    bool collapsed_in;   // the common post-sync state is held once: x in row 0, B2 in snap
+    bool collapsed_out;  // with sync: write the means to row 0 of x and to snap only
     int32_t algo;
 };
 
 hipError_t launch_step(const StepArgs &a, hipStream_t s);
 hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
-                       bool x_only, hipStream_t s);
+                       bool x_only, bool collapse, hipStream_t s);
+hipError_t launch_materialize(float *x, float *acc, const float *snap, int64_t d, int64_t pitch, int32_t W,
+                              hipStream_t s);
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
                        int32_t W, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);

@@ -196,18 +196,23 @@ template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const P
 //   y     = x - eta g / den ;  A2 = B2 + g o g
 //   SYNC: x, B2 <- mean over workers of y, A2; B2_sync <- that mean      (Synchronize branch)
 //   GRAD_ONLY: write g and change nothing (used to materialise gradients)
-template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY>
+// Right after a Synchronize every worker holds the same x and B2 = B2_sync.  With lazy replicas that common
+// state is kept once (x in row 0, B2 in snap):
+//   CIN : the state is collapsed on entry: read x from row 0 and B2 from snap for every worker
+//   COUT: (with SYNC) leave it collapsed: write the means to row 0 of x and to snap only
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool CIN, bool COUT>
 __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, const int32_t w_begin,
                                           const int32_t w_end)
 {
-    Pack<VEC> av, xs, step;
+    Pack<VEC> av, xs, step, sn, x0;
     if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
     if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
     if constexpr (!GRAD_ONLY) {
-        const Pack<VEC> sn = ld<VEC, false>(a.snap + j);
+        sn = ld<VEC, false>(a.snap + j);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) step.v[e] = a.eta / sqrtf(sn.v[e] + a.pad);
     }
+    if constexpr (CIN) x0 = ld<VEC, false>(a.x + j);
 
     Pack<VEC> sx, sb;
 #pragma unroll
@@ -218,8 +223,13 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
             const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
-            if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, NT_LD>(a.x + row);
-            if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, NT_LD>(a.acc + row);
+            if constexpr (CIN) {
+                xv[i] = x0;
+                if constexpr (!GRAD_ONLY) bv[i] = sn;
+            } else {
+                if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, NT_LD>(a.x + row);
+                if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, NT_LD>(a.acc + row);
+            }
         }
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
@@ -249,23 +259,28 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
         const float fw = (float)a.W;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
-        for (int32_t w = 0; w < a.W; ++w) {
-            const int64_t row = (int64_t)w * a.pitch + j;
-            st<VEC, NT_ST>(a.x + row, sx);
-            st<VEC, NT_ST>(a.acc + row, sb);
+        if constexpr (COUT) {
+            st<VEC, false>(a.x + j, sx);
+        } else {
+            for (int32_t w = 0; w < a.W; ++w) {
+                const int64_t row = (int64_t)w * a.pitch + j;
+                st<VEC, NT_ST>(a.x + row, sx);
+                st<VEC, NT_ST>(a.acc + row, sb);
+            }
         }
         st<VEC, false>(a.snap + j, sb);
     }
 }
 
-template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT>
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT, bool CIN, bool COUT>
 __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
 {
     static_assert(!SPLIT || (WT == 1 && !SYNC), "a split block owns one worker and cannot average");
+    static_assert(!COUT || SYNC, "only a step that averages can leave the state collapsed");
     int64_t j;
     int32_t w_begin, w_end;
     if (block_work<VEC, SPLIT>(a.d, a.W, &j, &w_begin, &w_end))
-        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY>(a, j, w_begin, w_end);
+        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT>(a, j, w_begin, w_end);
 }
 
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
 }
 
 // Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
-template <int VEC, int WT, bool X_ONLY>
+template <int VEC, int WT, bool X_ONLY, bool COUT>
 __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restrict__ acc, float *__restrict__ snap,
                                           int64_t pitch, int32_t W, const int64_t j)
 {
@@ -360,20 +375,40 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
     const float fw = (float)W;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
-    for (int32_t w = 0; w < W; ++w) {
-        st<VEC, NT_ST>(x + (int64_t)w * pitch + j, sx);
-        if constexpr (!X_ONLY) st<VEC, NT_ST>(acc + (int64_t)w * pitch + j, sb);
+    if constexpr (COUT) {
+        st<VEC, false>(x + j, sx);
+    } else {
+        for (int32_t w = 0; w < W; ++w) {
+            st<VEC, NT_ST>(x + (int64_t)w * pitch + j, sx);
+            if constexpr (!X_ONLY) st<VEC, NT_ST>(acc + (int64_t)w * pitch + j, sb);
+        }
     }
     if constexpr (!X_ONLY) st<VEC, false>(snap + j, sb);
 }
 
-template <int VEC, int WT, bool X_ONLY>
+template <int VEC, int WT, bool X_ONLY, bool COUT>
 __global__ __launch_bounds__(DBLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                      float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W)
 {
     int64_t j;
     int32_t w_begin, w_end;
-    if (block_work<VEC, false>(d, W, &j, &w_begin, &w_end)) mean_body<VEC, WT, X_ONLY>(x, acc, snap, pitch, W, j);
+    if (block_work<VEC, false>(d, W, &j, &w_begin, &w_end))
+        mean_body<VEC, WT, X_ONLY, COUT>(x, acc, snap, pitch, W, j);
+}
+
+// Undo the collapse: x[w] = x[0] for w >= 1, acc[w] = snap for every w.
+__global__ __launch_bounds__(BLOCK) void materialize_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                            const float *__restrict__ snap, int64_t d, int64_t pitch,
+                                                            int32_t W)
+{
+    const int64_t j = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (j >= d) return;
+    const float xv = x[j], bv = snap[j];
+    acc[j] = bv;
+    for (int32_t w = 1; w < W; ++w) {
+        x[(int64_t)w * pitch + j] = xv;
+        acc[(int64_t)w * pitch + j] = bv;
+    }
 }
 
 // Algorithm 3, Initialize: x[w] = x0 (or 0), acc = snap = b0^2.
@@ -594,15 +629,26 @@ static inline bool grid_for(int64_t n_threads, dim3 *grid)
 template <int VEC, int WT, int GS, int OS>
 static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
 {
+#define LAA_STEP(SYNC, GONLY, SPLIT, CIN, COUT) \
+    hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, SYNC, GONLY, SPLIT, CIN, COUT>), grid, dim3(DBLOCK), 0, s, a)
     if (a.grad_out) {
         if constexpr (GS == GRAD_EXPLICIT) return hipErrorInvalidValue;
-        else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, true, false>), grid, dim3(DBLOCK), 0, s, a);
+        else if (a.collapsed_in) LAA_STEP(false, true, false, true, false);
+        else LAA_STEP(false, true, false, false, false);
     } else if (a.algo == ALGO_LOCAL_ADAALTER) {
-        if (a.sync) hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, true, false, false>), grid, dim3(DBLOCK), 0, s, a);
-        else if (a.split) {
-            if constexpr (WT == 1) hipLaunchKernelGGL((step_kernel<VEC, 1, GS, OS, false, false, true>), grid, dim3(DBLOCK), 0, s, a);
+        if (a.sync) {
+            if (a.collapsed_in && a.collapsed_out) LAA_STEP(true, false, false, true, true);
+            else if (a.collapsed_in) LAA_STEP(true, false, false, true, false);
+            else if (a.collapsed_out) LAA_STEP(true, false, false, false, true);
+            else LAA_STEP(true, false, false, false, false);
+        } else if (a.collapsed_in) {
+            LAA_STEP(false, false, false, true, false);
+        } else if (a.split) {
+            if constexpr (WT == 1) LAA_STEP(false, false, true, false, false);
             else return hipErrorInvalidValue;
-        } else hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, false, false, false>), grid, dim3(DBLOCK), 0, s, a);
+        } else {
+            LAA_STEP(false, false, false, false, false);
+        }
     } else if (a.algo == ALGO_DIST_ADAGRAD) {
         hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(DBLOCK), 0, s, a);
     } else {
@@ -611,6 +657,7 @@ static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
         else
             hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, false>), grid, dim3(DBLOCK), 0, s, a);
     }
+#undef LAA_STEP
     return hipGetLastError();
 }
 
@@ -634,7 +681,9 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
     StepArgs a = a_in;
     if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0 || !layout_ok(a.d, a.pitch, a.vec4)) return hipErrorInvalidValue;
     // one worker per block only for the plain Local AdaAlter step (no averaging in the same pass)
-    a.split = a.split && a.vec4 && !a.sync && !a.grad_out && a.algo == ALGO_LOCAL_ADAALTER && a.W > 1;
+    a.split = a.split && a.vec4 && !a.sync && !a.grad_out && !a.collapsed_in && a.algo == ALGO_LOCAL_ADAALTER && a.W > 1;
+    if (a.algo != ALGO_LOCAL_ADAALTER && (a.collapsed_in || a.collapsed_out)) return hipErrorInvalidValue;
+    if (a.collapsed_out && !a.sync) return hipErrorInvalidValue;
     if (a.split) a.wt = 1;
     dim3 grid;
     if (a.vec4) {
@@ -653,30 +702,32 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
 
 template <int VEC, int WT>
 static hipError_t launch_mean_2(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool x_only,
-                                dim3 grid, hipStream_t s)
+                                bool collapse, dim3 grid, hipStream_t s)
 {
-    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
-    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
+    if (x_only) hipLaunchKernelGGL((mean_kernel<VEC, WT, true, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
+    else if (collapse) hipLaunchKernelGGL((mean_kernel<VEC, WT, false, true>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
+    else hipLaunchKernelGGL((mean_kernel<VEC, WT, false, false>), grid, dim3(DBLOCK), 0, s, x, acc, snap, d, pitch, W);
     return hipGetLastError();
 }
 
 hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pitch, int32_t W, bool vec4, int32_t wt,
-                       bool x_only, hipStream_t s)
+                       bool x_only, bool collapse, hipStream_t s)
 {
-    if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0 || !layout_ok(d, pitch, vec4)) return hipErrorInvalidValue;
+    if (d <= 0 || W <= 0 || wt <= 0 || W % wt != 0 || !layout_ok(d, pitch, vec4) || (x_only && collapse))
+        return hipErrorInvalidValue;
     dim3 grid;
     if (vec4) {
         if (d % 4 != 0 || !dense_grid(d / 4, false, W, &grid)) return hipErrorInvalidValue;
         switch (wt) {
-        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, pitch, W, x_only, grid, s);
-        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, pitch, W, x_only, grid, s);
-        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, pitch, W, x_only, grid, s);
-        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, pitch, W, x_only, grid, s);
+        case 1: return launch_mean_2<4, 1>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+        case 2: return launch_mean_2<4, 2>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+        case 4: return launch_mean_2<4, 4>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+        case 8: return launch_mean_2<4, 8>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
         }
         return hipErrorInvalidValue;
     }
     if (!dense_grid(d, false, W, &grid)) return hipErrorInvalidValue;
-    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, grid, s);
+    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
 }
 
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
@@ -685,6 +736,15 @@ hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float
     dim3 grid;
     if (!grid_for(d, &grid) || !layout_ok(d, pitch, false)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(init_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, x0, b0sq, d, pitch, W);
+    return hipGetLastError();
+}
+
+hipError_t launch_materialize(float *x, float *acc, const float *snap, int64_t d, int64_t pitch, int32_t W,
+                              hipStream_t s)
+{
+    dim3 grid;
+    if (!grid_for(d, &grid) || pitch < d) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(materialize_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, d, pitch, W);
     return hipGetLastError();
 }
 

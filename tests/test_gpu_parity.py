@@ -177,6 +177,90 @@ def test_fused_step_equals_local_step_plus_sync(B):
     assert torch.equal(a.x, b.x) and torch.equal(a.acc, b.acc) and torch.equal(a.snap, b.snap)
 
 
+@pytest.mark.parametrize("W,H,d,gen", [(8, 4, D_SMALL, False), (8, 4, D_SMALL, True), (4, 1, 4 * 500, True),
+                                         (3, 3, 1001, False), (2, 5, 4 * 64, True), (16, 2, 4 * 300, False)])
+def test_lazy_replicas_bit_identical_to_default(B, W, H, d, gen):
+    """With lazy replicas the post-sync state is kept once (row 0 of x, snap) until the next step; every
+    result must be bit-identical to the default mode, and match the oracle."""
+    import torch
+    say(f"lazy replicas W={W} H={H} d={d} gen={gen}")
+    rng = np.random.default_rng(23)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    ref = B.LocalAdaAlter(d, W, H, 0.5, 1.0); ref.init_state(dev(x0))
+    lz = B.LocalAdaAlter(d, W, H, 0.5, 1.0); lz.set_lazy_replicas(True); lz.init_state(dev(x0))
+    if gen:
+        o.set_generator(oracle.GEN_QUADRATIC, 3, a, xs, None, oracle.OFF_PHILOX, 0.1, 0.1)
+        for inst in (ref, lz):
+            inst.set_generator(B.GEN_QUADRATIC, 3, dev(a), dev(xs), None, B.OFF_PHILOX, 0.1, 0.1)
+    sc = parity.Scale(o)
+    for t in range(1, 3 * H + 2):
+        fused = t % 2 == 0 or H == 1                 # alternate the whole-iteration call with local step (+ sync)
+        if gen:
+            if t == H + 1:                           # a gradient read straight from the collapsed state
+                assert torch.equal(lz.generate_gradient(), ref.generate_gradient())
+            o.local_step_gen()
+            for inst in (ref, lz):
+                inst.step_gen() if fused else inst.local_step_gen()
+        else:
+            G = rng.standard_normal((W, d)).astype(np.float32)
+            o.local_step_dense(G)
+            for inst in (ref, lz):
+                inst.step_dense(dev(G)) if fused else inst.local_step_dense(dev(G))
+        sc.update(o)
+        if t % H == 0:
+            o.sync()
+            if not fused:
+                ref.sync(); lz.sync()
+            torch.cuda.synchronize()                 # collapsed: only row 0 of x and snap are current
+            assert torch.equal(lz.x[0], ref.x[0]) and torch.equal(lz.snap, ref.snap), f"collapsed state t={t}"
+        else:
+            torch.cuda.synchronize()
+            assert torch.equal(lz.x, ref.x) and torch.equal(lz.acc, ref.acc) and torch.equal(lz.snap, ref.snap), t
+        assert lz.counters() == ref.counters() == (o.t, o.steps_since_sync)
+    lz.materialize()
+    torch.cuda.synchronize()
+    assert torch.equal(lz.x, ref.x) and torch.equal(lz.acc, ref.acc) and torch.equal(lz.snap, ref.snap)
+    bar, fl = (1e-5, 1.0) if gen else (parity.FULL_RUN, parity.FLOOR_X)
+    parity.assert_state(host(lz.x), host(lz.acc), host(lz.snap), o, bar, floor_x=fl, what="lazy", scale=sc)
+
+
+def test_lazy_replicas_materialize_paths(B):
+    """Collapsed state followed by a sparse step, by switching the option off, and by an explicit materialize."""
+    import torch
+    W, H, rows, row_len = 4, 2, 50, 8
+    d = rows * row_len
+    rng = np.random.default_rng(29)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.set_lazy_replicas(True); g.init_state()
+    sc = parity.Scale(o)
+
+    def dense():
+        G = rng.standard_normal((W, d)).astype(np.float32)
+        o.step_dense(G); g.step_dense(dev(G)); sc.update(o)
+
+    dense(); dense()                                           # second one averages and leaves the state collapsed
+    idx = np.stack([rng.permutation(rows)[:10] for _ in range(W)]).astype(np.int32)
+    vals = rng.standard_normal((W, 10, row_len)).astype(np.float32)
+    o.local_step_sparse(idx, vals, row_len); g.local_step_sparse(dev(idx), dev(vals), row_len); sc.update(o)
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="sparse after collapse", scale=sc)
+    o.sync(); g.sync()                                         # sparse sync: rows only, never collapses
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="sparse sync", scale=sc)
+    dense(); dense()
+    g.set_lazy_replicas(False)                                 # expands the collapsed state
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="option off", scale=sc)
+    dense(); dense()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="default again", scale=sc)
+    g.set_lazy_replicas(True)
+    dense()
+    G = rng.standard_normal((W, d)).astype(np.float32)
+    o.local_step_dense(G); g.local_step_dense(dev(G)); sc.update(o)
+    o.sync(); g.sync()                                         # stand-alone mean kernel, collapsing
+    g.materialize(); g.materialize()                           # second call is a no-op
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="materialize", scale=sc)
+
+
 def test_sync_due_early_sync_and_noop_sync(B):
     W, H, d = 2, 2, 64
     g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
