@@ -37,6 +37,9 @@ def parse():
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
     p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
+    p.add_argument("--layout", default="auto", choices=["auto", "spread", "packed"],
+                   help="spread: all arrays of the quadratic workload 6 GB apart in one backing allocation "
+                        "(binding.spread_buffers); packed: separate dense tensors; auto: spread for c5")
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -104,12 +107,20 @@ def main():
     d, W = c.d, c.W
 
     pitch = args.pitch or None
+    spread = c.kind == "quadratic" and (args.layout == "spread" or (args.layout == "auto" and c.name == "c5"))
     extra = []          # further state machines stepped in the same iteration (c4's dense blocks)
     if c.kind == "quadratic":
-        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+        if spread:
+            rd = max(wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
+            backing, bx, bacc, bsnap, a, xs = B.spread_buffers(d, W, rd, dev)
+            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rd)
+            a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
+            xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
+        else:
+            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+            a = torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)).to(dev)
+            xs = torch.from_numpy(wl.optimum(d, c.seed)).to(dev)
         g.init_state()
-        a = torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)).to(dev)
-        xs = torch.from_numpy(wl.optimum(d, c.seed)).to(dev)
         off = None
         if args.offsets == "array":
             off = g.rows()
@@ -154,7 +165,7 @@ def main():
                     for t in range(P)]
         vals_pool = [torch.randn((W, c.k, c.row_len), dtype=torch.float32, device=dev) * c.val_sigma for _ in range(4)]
         dd = sum(r * q for r, q in c.dense_blocks)
-        gd = B.LocalAdaAlter(dd, W, H, c.eta, c.eps, pitch=pitch)
+        gd = B.LocalAdaAlter(dd, W, H, c.eta, c.eps)
         gd.init_state()
         sigd = torch.from_numpy(wl.sigma(dd, c.seed)).to(dev)
         gd.set_generator(B.GEN_NOISE, c.seed, sigd)
@@ -226,7 +237,8 @@ def main():
         "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
-                               f"lazy_replicas={'on' if lazy else 'off'} row_pitch={g.pitch}",
+                               f"lazy_replicas={'on' if lazy else 'off'} layout={'spread' if spread else 'packed'} "
+                               f"row_pitch={g.pitch}",
                    "syncs_in_timed_region": len(sync_it),
                    "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
                    "ms_post_sync_iteration": (sum(post_sync) / len(post_sync)) if post_sync else None,

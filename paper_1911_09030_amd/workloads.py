@@ -54,6 +54,9 @@ WORKLOADS = {
 }
 
 
+SPREAD_ROW_DISTANCE = 1_500_000_000     # elements (6 GB) between the rows of the benchmark's spread layout
+
+
 def _rng(seed: int, stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
 

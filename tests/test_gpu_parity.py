@@ -447,8 +447,9 @@ def test_adagrad_and_local_sgd_variants(B, W, d):
 
 
 # ------------------------------------------------------------------------------------------ benchmark configurations
-def _quadratic_setup(B, c, n_groups, off_mode="philox"):
-    """GPU instance at the full size of workload c and an oracle that follows a sample of its columns."""
+def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
+    """GPU instance at the full size of workload c and an oracle that follows a sample of its columns.
+    bench_layout: the launch configuration bench.py times (spread row pitch, lazy replicas)."""
     cols = wl.column_sample(c.d, n_groups, seed=1)
     a = wl.curvature(c.d, c.seed, c.a_dist)
     xs = wl.optimum(c.d, c.seed)
@@ -456,8 +457,18 @@ def _quadratic_setup(B, c, n_groups, off_mode="philox"):
     o = Oracle(len(cols), c.W, c.H, c.eta, c.eps)
     o.set_columns(cols); o.init_state()
     o.set_generator(oracle.GEN_QUADRATIC, c.seed, a[cols], xs[cols], None, om, c.noise_scale, c.off_scale)
-    g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps); g.init_state()
-    g.set_generator(B.GEN_QUADRATIC, c.seed, dev(a), dev(xs), None, om, c.noise_scale, c.off_scale)
+    if bench_layout:
+        import torch
+        rd = max(wl.SPREAD_ROW_DISTANCE, c.d)
+        backing, bx, bacc, bsnap, da, dxs = B.spread_buffers(c.d, c.W, rd)
+        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rd)
+        g.set_lazy_replicas(True)
+        da.copy_(torch.from_numpy(a)); dxs.copy_(torch.from_numpy(xs))
+    else:
+        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps)
+        da, dxs = dev(a), dev(xs)
+    g.init_state()
+    g.set_generator(B.GEN_QUADRATIC, c.seed, da, dxs, None, om, c.noise_scale, c.off_scale)
     return cols, o, g
 
 
@@ -497,12 +508,13 @@ def test_config5_headline_size_two_periods_on_sampled_columns(B):
     """d=400M, W=8, H=16 in the launch configuration the benchmark times (fused step, Philox offsets)."""
     import torch
     c = wl.WORKLOADS["c5"]
-    cols, o, g = _quadratic_setup(B, c, 512)
+    cols, o, g = _quadratic_setup(B, c, 512, bench_layout=True)
     for t in range(1, 2 * c.H + 1):
         o.step_gen(); g.step_gen()
         if t == 1:
             parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
                                 floor_x=1.0, what="c5 t=1")
+    g.materialize()                                   # the last iteration averaged: expand the collapsed state
     e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
                             floor_x=1.0, what="c5")
     say("   c5 rel err", e)
