@@ -148,6 +148,32 @@ def test_pitched_rows(B, W, d, pitch):
             g.step_dense(dev(np.zeros((W, d), np.float32)))
 
 
+def test_spread_buffers_layout(B):
+    """binding.spread_buffers: 2W + 3 arrays a fixed distance apart in one allocation, usable as the state."""
+    import torch
+    W, d, rd, H = 4, 4 * 300, 4 * 1000, 2
+    backing, x, acc, snap, a, xs = B.spread_buffers(d, W, rd)
+    assert backing.numel() == (2 * W + 3) * rd and x.shape == (W, d) and x.stride(0) == rd
+    base = backing.data_ptr()
+    assert [t.data_ptr() - base for t in (x, acc, snap, a, xs)] == [0, 4 * W * rd, 8 * W * rd, 4 * (2 * W + 1) * rd,
+                                                                   4 * (2 * W + 2) * rd]
+    backing.fill_(7.0)
+    rng = np.random.default_rng(31)
+    an = rng.uniform(0.1, 10, d).astype(np.float32); xn = rng.standard_normal(d).astype(np.float32)
+    a.copy_(torch.from_numpy(an)); xs.copy_(torch.from_numpy(xn))
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0, x=x, acc=acc, snap=snap, pitch=rd); g.set_lazy_replicas(True); g.init_state()
+    g.set_generator(B.GEN_QUADRATIC, 1, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    o.set_generator(oracle.GEN_QUADRATIC, 1, an, xn, None, oracle.OFF_PHILOX, 0.1, 0.1)
+    for _ in range(2 * H + 1):
+        o.step_gen(); g.step_gen()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="spread buffers")
+    full = backing.view(2 * W + 3, rd)
+    assert bool((full[:, d:] == 7.0).all()), "the gaps between the arrays were written"
+    with pytest.raises(ValueError):
+        B.spread_buffers(d, W, d - 4)
+
+
 def test_fused_step_equals_local_step_plus_sync(B):
     import torch
     W, H, d = 8, 3, D_SMALL
