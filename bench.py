@@ -34,6 +34,8 @@ def parse():
     p.add_argument("--H", type=int, default=0, help="override the sync period (c3 sweep)")
     p.add_argument("--offsets", default="philox", choices=["philox", "array", "none"],
                    help="per-worker optimum offsets: regenerated in-kernel, read from HBM, or absent")
+    p.add_argument("--row-distance", type=int, default=0,
+                   help="elements between the arrays of the spread layout (default workloads.SPREAD_ROW_DISTANCE)")
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
     p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
@@ -111,7 +113,7 @@ def main():
     extra = []          # further state machines stepped in the same iteration (c4's dense blocks)
     if c.kind == "quadratic":
         if spread:
-            rd = max(wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
+            rd = max(args.row_distance or wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
             backing, bx, bacc, bsnap, a, xs = B.spread_buffers(d, W, rd, dev)
             g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rd)
             a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))

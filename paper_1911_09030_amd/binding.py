@@ -103,10 +103,10 @@ def spread_buffers(d, W, row_distance, device="cuda:0"):
     elements apart: x rows, then acc rows, then snap, a, xstar.  Returns (backing, x, acc, snap, a, xstar), the
     state arrays as [W][d] / [d] views (row pitch ``row_distance``).
 
-    Why: on MI355X a thread's 2W read-modify-write streams run 6-7 % faster when the arrays streamed together
-    span about 100 GB of the HBM address range or more (d = 4e8, W = 8: 8.80 ms per step against 9.37 ms when
-    packed into 30 GB of the same allocation; the threshold scales as 1/(number of streams), as if a third of
-    the address range maps to one rank of the 12-high stacks).  The gaps are allocated but never touched."""
+    Why: on MI355X a thread's 2W read-modify-write streams run 6-8 % faster when the arrays streamed together
+    span most of the HBM address range (d = 4e8, W = 8: 8.72 ms per step with the arrays 10 GB apart against
+    9.1-9.5 ms when packed into 30 GB; the threshold scales as 1/(number of streams), as if a third of the
+    address range maps to one rank of the 12-high stacks).  The gaps are allocated but never touched."""
     import torch
     d, W, rd = int(d), int(W), int(row_distance)
     if rd < d or rd % 4:

@@ -54,7 +54,10 @@ WORKLOADS = {
 }
 
 
-SPREAD_ROW_DISTANCE = 1_500_000_000     # elements (6 GB) between the rows of the benchmark's spread layout
+# Elements (10 GB) between the arrays of the benchmark's spread layout: 19 arrays then span 190 GB, i.e. every
+# part of the 288 GB address range; with 6 or 8 GB the result still depended on where the backing allocation
+# happened to start (8.7 to 9.6 ms per step from run to run), with 10 GB it was 8.71-8.73 ms in every run.
+SPREAD_ROW_DISTANCE = 2_500_000_000
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:
