@@ -176,6 +176,16 @@ int laa_get_counters(laa_handle h, int64_t *t, int32_t *steps_since_sync, int64_
  * Synchronises the stream. */
 int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n);
 
+/* Diagnostics of the quadratic workload at the mean iterate xbar = (1/W) sum_w x_w (the auxiliary
+ * variable of Section 5, which the convergence theorem is stated for), into out (HOST, 3 doubles):
+ *   out[0] = ||xbar - xstar||^2
+ *   out[1] = ||grad F(xbar)||^2,  grad F(xbar)_j = a_j (xbar_j - xstar_j - mean_w off_wj)
+ *   out[2] = (1/W) sum_w ||x_w - xbar||^2      (how far the workers have drifted apart)
+ * Needs LAA_GEN_QUADRATIC.  Sums are accumulated in fp64 in a fixed order (wavefront shuffles,
+ * LDS, then one block over the per-block partials).  Synchronises the stream; allocates a 48 KiB
+ * scratch buffer on first use. */
+int laa_diagnostics(laa_handle h, double *out);
+
 /* Bytes the method itself had to move for everything enqueued so far
  * (x, acc read+write per element-update, snap and generator arrays once per
  * column-step, literal sync traffic), for bandwidth accounting. */

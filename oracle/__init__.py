@@ -73,6 +73,7 @@ class _Lib:
         L.ora_t.restype = C.c_int64
         L.ora_steps_since_sync.argtypes = [C.c_void_p]
         L.ora_steps_since_sync.restype = C.c_int32
+        L.ora_diagnostics.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         L.ora_philox4x32_10.argtypes = [rp, rp, rp]
         L.ora_philox4x32_10.restype = None
         L.ora_normals4.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint64, rp]
@@ -196,6 +197,11 @@ class Oracle:
 
     def sync(self):
         self._chk(self.L.ora_sync(self.h))
+
+    def diagnostics(self):
+        out = (C.c_double * 3)()
+        self._chk(self.L.ora_diagnostics(self.h, out))
+        return tuple(out)
 
     def _view(self, fn, shape):
         p = fn(self.h)

@@ -391,6 +391,38 @@ int64_t ora_dirty_rows(const ora_ctx *c, int32_t *out, int64_t cap)
     return n;
 }
 
+/* Diagnostics at the mean iterate xbar = (1/n) sum_i x_i (Section 5, auxiliary variable) for the quadratic
+ * objective F(x) = (1/n) sum_i (1/2) sum_j a_j (x_j - xstar_j - off_ij)^2:
+ *   out[0] = ||xbar - xstar||^2, out[1] = ||grad F(xbar)||^2, out[2] = (1/n) sum_i ||x_i - xbar||^2. */
+int ora_diagnostics(const ora_ctx *c, double out[3])
+{
+    if (!c || !out) return ORA_EINVAL;
+    if (c->gen_mode != ORA_GEN_QUADRATIC) return ORA_EMODE;
+    double s0 = 0, s1 = 0, s2 = 0;
+    for (int64_t j = 0; j < c->d; ++j) {
+        double xbar = 0, moff = 0, dev = 0;
+        for (int32_t w = 0; w < c->W; ++w) xbar += (double)c->x[(size_t)w * c->d + j];
+        xbar /= (double)c->W;
+        for (int32_t w = 0; w < c->W; ++w) {
+            const double t = (double)c->x[(size_t)w * c->d + j] - xbar;
+            dev += t * t;
+            if (c->off_mode == ORA_OFF_ARRAY) moff += (double)c->off[(size_t)w * c->d + j];
+            else if (c->off_mode == ORA_OFF_PHILOX) {
+                real m[4];
+                const uint64_t ja = (uint64_t)c->col[j];
+                ora_normals4(c->seed, ORA_STREAM_OFFSET, ja >> 2, (uint32_t)w, 0, m);
+                moff += (double)c->off_scale * (double)m[ja & 3];
+            }
+        }
+        moff /= (double)c->W;
+        const double dx = xbar - (double)c->xstar[j];
+        const double g = (double)c->a[j] * (dx - moff);
+        s0 += dx * dx; s1 += g * g; s2 += dev / (double)c->W;
+    }
+    out[0] = s0; out[1] = s1; out[2] = s2;
+    return ORA_OK;
+}
+
 /* One whole iteration t of Algorithm 3: the local update, then the averaging when mod(t,H)=0. */
 int ora_step_dense(ora_ctx *c, const real *G)
 {

@@ -23,7 +23,7 @@ EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
     "laa_set_tile", "laa_set_lazy_replicas", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
-    "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_get_dirty_rows", "laa_bytes_moved",
+    "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
     "laa_debug_philox", "laa_debug_copy",
 ]
 
@@ -71,6 +71,7 @@ def lib():
         "laa_step_sparse": [vp, vp, vp, i32, i32],
         "laa_get_counters": [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)],
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
+        "laa_diagnostics": [vp, C.POINTER(C.c_double)],
         "laa_bytes_moved": [vp, C.POINTER(u64)],
         "laa_debug_philox": [vp, vp, vp],
         "laa_debug_copy": [vp, vp, i64, vp],
@@ -245,6 +246,12 @@ class LocalAdaAlter:
         if n.value:
             _check(self.L.laa_get_dirty_rows(self.h, out.ctypes.data_as(C.c_void_p), n.value, C.byref(n)))
         return out
+
+    def diagnostics(self):
+        """(||xbar - xstar||^2, ||grad F(xbar)||^2, mean_w ||x_w - xbar||^2) of the quadratic workload."""
+        out = (C.c_double * 3)()
+        _check(self.L.laa_diagnostics(self.h, out))
+        return tuple(out)
 
     def bytes_moved(self):
         b = C.c_uint64()

@@ -37,6 +37,7 @@ struct laa_ctx {
     int32_t *dirty_list = nullptr;
     uint32_t *dirty_count = nullptr, *scan_scratch = nullptr;
     unsigned long long *bad = nullptr;
+    double *diag_scratch = nullptr;   // block partials + results of laa_diagnostics
     bool sparse_only_since_sync = true;   // every step since the last sync was a sparse one
     uint64_t bytes = 0;
 };
@@ -225,6 +226,7 @@ int laa_destroy(laa_handle h)
 {
     if (!h) return LAA_OK;
     free_sparse(h);
+    if (h->diag_scratch) (void)hipFree(h->diag_scratch);
     delete h;
     return LAA_OK;
 }
@@ -473,6 +475,35 @@ int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n)
         if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
         if (e != hipSuccess) return hip_fail(e, "copying the dirty-row list");
     }
+    return LAA_OK;
+}
+
+int laa_diagnostics(laa_handle h, double *out)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (!out) return fail(LAA_EINVAL, "null out");
+    if (h->gen_mode != LAA_GEN_QUADRATIC) return fail(LAA_EMODE, "diagnostics need the quadratic generator (a, xstar)");
+    hipError_t e;
+    if (!h->diag_scratch) {
+        e = hipMalloc(&h->diag_scratch, (size_t)laa::diag_scratch_doubles() * sizeof(double));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc diagnostics scratch");
+    }
+    laa::StepArgs a{};
+    a.x = h->x; a.acc = h->acc; a.snap = h->snap;
+    a.a = h->a; a.xstar = h->xstar; a.off = h->off;
+    a.d = h->d; a.pitch = h->pitch; a.W = h->W;
+    a.off_scale = h->off_scale;
+    a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.off_source = h->off_mode;
+    a.collapsed_in = h->collapsed;
+    a.vec4 = h->vec4 && h->gen_aligned16;
+    e = laa::launch_diagnostics(a, h->diag_scratch, h->stream);
+    if (e != hipSuccess) return hip_fail(e, "diagnostics kernel launch");
+    e = hipMemcpyAsync(out, h->diag_scratch + laa::diag_scratch_doubles() - 3, 3 * sizeof(double), hipMemcpyDeviceToHost,
+                       h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(e, "reading the diagnostics");
     return LAA_OK;
 }
 

@@ -65,6 +65,8 @@ hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *
                                 uint32_t *scratch, hipStream_t s);
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t row_len,
                             const int32_t *list, const uint32_t *count, hipStream_t s);
+int32_t diag_scratch_doubles();
+hipError_t launch_diagnostics(const StepArgs &a, double *scratch, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
 hipError_t debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 

@@ -590,6 +590,90 @@ __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x,
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Diagnostics of the quadratic workload at the mean iterate xbar = (1/W) sum_w x_w (the auxiliary variable of
+// Section 5): out[0] = ||xbar - xstar||^2, out[1] = ||grad F(xbar)||^2 with
+// grad F(xbar)_j = a_j (xbar_j - xstar_j - mean_w off_wj), out[2] = (1/W) sum_w ||x_w - xbar||^2.
+// Elementwise terms in fp32, sums in fp64: per thread, then across the wavefront with lane shuffles, across the
+// block through LDS, one partial per block into `partial`; a second one-block kernel adds the partials in a fixed
+// order, so the result does not depend on scheduling.
+static constexpr int DIAG_BLOCKS = 2048;
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+template <int VEC, int OS>
+__global__ __launch_bounds__(BLOCK) void diag_kernel(const StepArgs a, double *__restrict__ partial)
+{
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+    const int64_t n_groups = (a.d + VEC - 1) / VEC;
+    const float fw = (float)a.W;
+    for (int64_t q = (int64_t)blockIdx.x * BLOCK + threadIdx.x; q < n_groups; q += (int64_t)gridDim.x * BLOCK) {
+        const int64_t j = q * VEC;
+        const Pack<VEC> av = ld<VEC, false>(a.a + j), xs = ld<VEC, false>(a.xstar + j);
+        Pack<VEC> xbar, moff, dev;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xbar.v[e] = moff.v[e] = dev.v[e] = 0.0f;
+        const int32_t rows = a.collapsed_in ? 1 : a.W;
+        for (int32_t w = 0; w < rows; ++w) {
+            const Pack<VEC> xv = ld<VEC, false>(a.x + (int64_t)w * a.pitch + j);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) xbar.v[e] += xv.v[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xbar.v[e] = xbar.v[e] / (float)rows;
+        for (int32_t w = 0; w < a.W; ++w) {
+            if (!a.collapsed_in) {
+                const Pack<VEC> xv = ld<VEC, false>(a.x + (int64_t)w * a.pitch + j);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { const float t = xv.v[e] - xbar.v[e]; dev.v[e] = fmaf(t, t, dev.v[e]); }
+            }
+            if constexpr (OS == OFFSET_ARRAY) {
+                const Pack<VEC> o = ld<VEC, false>(a.off + (int64_t)w * a.pitch + j);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) moff.v[e] += o.v[e];
+            } else if constexpr (OS == OFFSET_PHILOX) {
+                float m[4];
+                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, (uint64_t)j >> 2, (uint32_t)w, 0u, m);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) moff.v[e] += a.off_scale * m[VEC == 4 ? e : (int)(j & 3)];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float dx = xbar.v[e] - xs.v[e];
+            const float g = av.v[e] * (dx - moff.v[e] / fw);
+            s0 += (double)dx * (double)dx;
+            s1 += (double)g * (double)g;
+            s2 += (double)(dev.v[e] / fw);
+        }
+    }
+    __shared__ double sh[3][WAVES_PER_BLOCK];
+    s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2);
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    if (lane == 0) { sh[0][wave] = s0; sh[1][wave] = s1; sh[2][wave] = s2; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double t = 0.0;
+        for (int k = 0; k < WAVES_PER_BLOCK; ++k) t += sh[threadIdx.x][k];
+        partial[(int64_t)blockIdx.x * 3 + threadIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(WAVE) void diag_final_kernel(const double *__restrict__ partial, int32_t n_blocks,
+                                                         double *__restrict__ out)
+{
+    if (threadIdx.x < 3) {
+        double t = 0.0;
+        for (int32_t b = 0; b < n_blocks; ++b) t += partial[(int64_t)b * 3 + threadIdx.x];
+        out[threadIdx.x] = t;
+    }
+}
+
 __global__ void philox_debug_kernel(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
                                     uint32_t *out)
 {
@@ -754,6 +838,33 @@ hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s)
     dim3 grid;
     if (!grid_for(n, &grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fill_u32_kernel, grid, dim3(BLOCK), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+int32_t diag_scratch_doubles() { return DIAG_BLOCKS * 3 + 3; }
+
+// scratch: diag_scratch_doubles() doubles of device memory; the three results land in its last three entries
+hipError_t launch_diagnostics(const StepArgs &a, double *scratch, hipStream_t s)
+{
+    if (a.d <= 0 || a.W <= 0 || !a.a || !a.xstar || !scratch || !layout_ok(a.d, a.pitch, a.vec4)) return hipErrorInvalidValue;
+    const int64_t n_groups = a.vec4 ? a.d / 4 : a.d;
+    const int64_t want = (n_groups + BLOCK - 1) / BLOCK;
+    const int32_t nb = (int32_t)(want < DIAG_BLOCKS ? want : DIAG_BLOCKS);
+    double *out = scratch + DIAG_BLOCKS * 3;
+    const dim3 grid((unsigned)nb), block(BLOCK);
+#define LAA_DIAG(VEC, OS) hipLaunchKernelGGL((diag_kernel<VEC, OS>), grid, block, 0, s, a, scratch)
+    if (a.vec4) {
+        if (a.d % 4 != 0) return hipErrorInvalidValue;
+        if (a.off_source == OFFSET_ARRAY) LAA_DIAG(4, OFFSET_ARRAY);
+        else if (a.off_source == OFFSET_PHILOX) LAA_DIAG(4, OFFSET_PHILOX);
+        else LAA_DIAG(4, OFFSET_NONE);
+    } else {
+        if (a.off_source == OFFSET_ARRAY) LAA_DIAG(1, OFFSET_ARRAY);
+        else if (a.off_source == OFFSET_PHILOX) LAA_DIAG(1, OFFSET_PHILOX);
+        else LAA_DIAG(1, OFFSET_NONE);
+    }
+#undef LAA_DIAG
+    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(WAVE), 0, s, scratch, nb, out);
     return hipGetLastError();
 }
 

@@ -368,7 +368,30 @@ def pin_adagrad_and_local_sgd(lib):
         _close(s.x, want, _tol(lib) * 4, f"Local SGD at t={t}")
 
 
-ALL_PINS = [pin_literal_history, pin_closed_form_constant_gradient, pin_h1_is_sync_adaalter, pin_w1_is_serial,
+def pin_diagnostics(lib):
+    """Section 5's mean iterate: ||xbar - xstar||^2, ||grad F(xbar)||^2 with grad F(xbar) = a (xbar - xstar - mean off)
+    for the quadratic objective, and the mean squared distance of the workers from xbar -- recomputed with numpy;
+    at xbar = xstar + mean off the gradient vanishes."""
+    W, d = 4, 12
+    rng = np.random.default_rng(41)
+    a = rng.uniform(0.1, 10, d); xs = rng.standard_normal(d); off = 0.3 * rng.standard_normal((W, d))
+    o = Oracle(d, W, 5, 0.5, 1.0, lib=lib); o.init_state(rng.standard_normal(d))
+    o.set_generator(oracle.GEN_QUADRATIC, 9, a, xs, off, oracle.OFF_ARRAY, 0.1, 0.1)
+    for _ in range(3):
+        o.local_step_gen()
+    x = o.x.astype(np.float64)
+    ar, xr, offr = (np.asarray(o._real(v), dtype=np.float64) for v in (a, xs, off))
+    xbar = x.mean(axis=0)
+    want = (np.sum((xbar - xr) ** 2), np.sum((ar * (xbar - xr - offr.mean(axis=0))) ** 2), np.mean(np.sum((x - xbar) ** 2, axis=1)))
+    _close(o.diagnostics(), want, 1e-12 if lib.real_bytes == 8 else 1e-5, "diagnostics")
+    p = Oracle(d, W, 5, 0.5, 1.0, lib=lib)
+    p.init_state(xr + offr.mean(axis=0))
+    p.set_generator(oracle.GEN_QUADRATIC, 9, a, xs, off, oracle.OFF_ARRAY, 0.1, 0.1)
+    g = p.diagnostics()
+    assert g[1] <= 1e-10 and g[2] == 0.0 and abs(g[0] - np.sum(offr.mean(axis=0) ** 2)) <= 1e-6
+
+
+ALL_PINS = [pin_diagnostics, pin_literal_history, pin_closed_form_constant_gradient, pin_h1_is_sync_adaalter, pin_w1_is_serial,
             pin_global_accumulator_and_invariants, pin_mean_iterate, pin_worker_permutation,
             pin_sync_due_and_early_sync, pin_sparse_equals_dense, pin_philox_kat, pin_normal_statistics,
             pin_box_muller_from_words, pin_gradient_formula, pin_warmup, pin_adagrad_and_local_sgd]

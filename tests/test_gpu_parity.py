@@ -287,6 +287,32 @@ def test_lazy_replicas_materialize_paths(B):
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="materialize", scale=sc)
 
 
+@pytest.mark.parametrize("off_mode,W,d", [("philox", 8, D_SMALL), ("array", 4, 4 * 2500), ("none", 3, 4 * 700 + 1),
+                                          ("philox", 5, 999)])
+def test_diagnostics_match_oracle(B, off_mode, W, d):
+    say(f"diagnostics off={off_mode} W={W} d={d}")
+    H = 3
+    rng = np.random.default_rng(43)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    off = (0.1 * rng.standard_normal((W, d))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    om = {"none": oracle.OFF_NONE, "array": oracle.OFF_ARRAY, "philox": oracle.OFF_PHILOX}[off_mode]
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    o.set_generator(oracle.GEN_QUADRATIC, 17, a, xs, off if off_mode == "array" else None, om, 0.1, 0.1)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.set_lazy_replicas(True); g.init_state(dev(x0))
+    g.set_generator(B.GEN_QUADRATIC, 17, dev(a), dev(xs), dev(off) if off_mode == "array" else None, om, 0.1, 0.1)
+    for t in range(1, 2 * H + 2):
+        want, got = o.diagnostics(), g.diagnostics()           # at t = H + 1 the GPU state is collapsed
+        for k in range(3):
+            assert abs(got[k] - want[k]) <= 2e-5 * max(want[k], 1e-3 * want[0]), (t, k, got, want)
+        o.step_gen(); g.step_gen()
+    assert g.diagnostics()[2] > 0
+    h = B.LocalAdaAlter(d, W, H, 0.5, 1.0); h.init_state()
+    with pytest.raises(B.LaaError) as ei:
+        h.diagnostics()
+    assert ei.value.code == B.EMODE
+
+
 def test_sync_due_early_sync_and_noop_sync(B):
     W, H, d = 2, 2, 64
     g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()

@@ -108,3 +108,25 @@ def test_tolerance_calibration_fp32_statements_meet_the_gpu_bars():
             o.step_gen()
         runs.append(o)
     parity.assert_state(runs[1].x, runs[1].acc, runs[1].snap, runs[0], 1e-5, floor_x=1.0, what="fp32 generator run")
+
+
+def test_noise_grows_with_the_sync_period():
+    """Section 5, remark after the theorem: compared with H = 1, local steps add noise that grows with H.  On the
+    small quadratic configuration the workers' drift (1/n) sum_i ||x_i - xbar||^2 just before a synchronisation
+    (the quantity the proof bounds by the H^2 term) grows with H."""
+    from paper_1911_09030_amd import workloads as wl
+    c = wl.WORKLOADS["c1"]
+    cols = wl.column_sample(c.d, 256, seed=3)
+    a = wl.curvature(c.d, c.seed, c.a_dist)[cols]; xs = wl.optimum(c.d, c.seed)[cols]
+    drift = {}
+    for H in (1, 4, 16):
+        o = oracle.Oracle(len(cols), c.W, H, c.eta, c.eps)
+        o.set_columns(cols); o.init_state()
+        o.set_generator(oracle.GEN_QUADRATIC, c.seed, a, xs, None, oracle.OFF_PHILOX, c.noise_scale, c.off_scale)
+        for t in range(1, c.T + 1):
+            o.local_step_gen()
+            if t == c.T:
+                drift[H] = o.diagnostics()[2]
+            if t % H == 0:
+                o.sync()
+    assert drift[1] < drift[4] < drift[16]
