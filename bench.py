@@ -49,6 +49,10 @@ def parse():
                    help="after the run, launch the plain copy kernel this many times over one row of d floats "
                         "(a known volume for scaling profiler byte counters)")
     p.add_argument("--cpu-sample-d", type=int, default=524_288)
+    p.add_argument("--cpu-procs", type=int, default=min(16, os.cpu_count() or 1),
+                   help="processes of the all-cores CPU baseline (1 switches it off)")
+    p.add_argument("--cpu-slice", type=int, nargs=2, metavar=("LO", "N"), default=None,
+                   help="internal: run the oracle on columns [LO, LO+N) and print the seconds")
     return p.parse_args()
 
 
@@ -64,31 +68,53 @@ def traffic_from_profile(kernel_tag: str):
     return None
 
 
-def cpu_baseline(c, sample_d, offsets):
-    """The oracle as it stands (single thread, fp64) on a column slice of the same workload: one sync period."""
+def _oracle_period(c, lo, n, offsets):
+    """One sync period of the fp64 oracle on the columns [lo, lo + n) of workload c; returns the seconds it took."""
     import numpy as np
     import oracle
     from paper_1911_09030_amd import workloads as wl
-    cols = np.arange(sample_d, dtype=np.int64)
-    a = wl.curvature(sample_d, c.seed, c.a_dist)
-    xs = wl.optimum(sample_d, c.seed)
-    o = oracle.Oracle(sample_d, c.W, c.H, c.eta, c.eps)
+    cols = np.arange(lo, lo + n, dtype=np.int64)
+    a = wl.curvature(lo + n, c.seed, c.a_dist)[lo:]
+    xs = wl.optimum(lo + n, c.seed)[lo:]
+    o = oracle.Oracle(n, c.W, c.H, c.eta, c.eps)
     o.set_columns(cols)
     o.init_state()
     om = {"philox": oracle.OFF_PHILOX, "none": oracle.OFF_NONE, "array": oracle.OFF_ARRAY}[offsets]
-    off = wl.offsets(sample_d, c.W, c.seed, c.off_scale) if offsets == "array" else None
+    off = wl.offsets(lo + n, c.W, c.seed, c.off_scale)[:, lo:] if offsets == "array" else None
     o.set_generator(oracle.GEN_QUADRATIC, c.seed, a, xs, off, om, c.noise_scale, c.off_scale)
     t0 = time.perf_counter()
     for _ in range(c.H):
         o.step_gen()
-    dt = time.perf_counter() - t0
-    return {"value": c.W * sample_d * c.H / dt, "unit": "element-updates/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {sample_d} columns of {c.name}, W={c.W}, one sync period of H={c.H} steps, fp64, "
-                      f"{dt:.1f} s"}
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(c, sample_d, offsets, procs):
+    """The oracle as it stands (single thread, fp64) on a column slice of the same workload, one sync period; then
+    the same oracle as `procs` independent single-threaded processes on disjoint column slices (columns are
+    independent, so this is the same computation)."""
+    import subprocess
+    dt = _oracle_period(c, 0, sample_d, offsets)
+    out = {"value": c.W * sample_d * c.H / dt, "unit": "element-updates/s", "cores": 1, "kind": "oracle",
+           "sample": f"first {sample_d} columns of {c.name}, W={c.W}, one sync period of H={c.H} steps, fp64, "
+                     f"{dt:.1f} s"}
+    if procs > 1:
+        kids = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--workload", c.name, "--offsets", offsets,
+                                  "--cpu-slice", str(i * sample_d), str(sample_d)], stdout=subprocess.PIPE, text=True)
+                for i in range(procs)]
+        times = [float(k.communicate()[0].strip().splitlines()[-1]) for k in kids]
+        if all(k.returncode == 0 for k in kids):
+            out["all_cores"] = {"value": procs * c.W * sample_d * c.H / max(times), "unit": "element-updates/s",
+                                "cores": procs, "kind": "oracle",
+                                "sample": f"{procs} processes x {sample_d} disjoint columns, slowest {max(times):.1f} s"}
+    return out
 
 
 def main():
     args = parse()
+    if args.cpu_slice:                      # child of the all-cores CPU baseline: no GPU, no torch
+        from paper_1911_09030_amd import workloads as wl
+        print(_oracle_period(wl.WORKLOADS[args.workload], args.cpu_slice[0], args.cpu_slice[1], args.offsets))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W workers are a worker axis in one GPU's HBM); "
               "--gpus must be 1", file=sys.stderr)
@@ -251,7 +277,7 @@ def main():
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     if not args.no_cpu_baseline and c.kind == "quadratic":
-        out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets)
+        out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets, args.cpu_procs)
     print(json.dumps(out), flush=True)
 
 
