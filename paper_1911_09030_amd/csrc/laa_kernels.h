@@ -11,7 +11,7 @@ enum OffsetSource { OFFSET_NONE = 0, OFFSET_ARRAY = 1, OFFSET_PHILOX = 2 };
 enum Algo { ALGO_LOCAL_ADAALTER = 0, ALGO_DIST_ADAGRAD = 1, ALGO_LOCAL_SGD = 2 };
 
 struct StepArgs {
-    float *x;            // [W][pitch], d used
+    float *x;            // [W][pitch], the first d entries of each row used
     float *acc;          // [W][pitch]
     float *snap;         // [d]
     const float *grads;  // [W][d] explicit gradients, or null

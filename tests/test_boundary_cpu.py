@@ -65,6 +65,13 @@ def test_host_error_paths(L):
     assert L.laa_set_generator(h, binding.GEN_QUADRATIC, 0, C.c_void_p(16), C.c_void_p(32), None,
                                binding.OFF_ARRAY, .1, .1) == binding.EINVAL
     assert L.laa_set_generator(h, binding.GEN_NOISE, 0, C.c_void_p(18), None, None, 0, .1, .1) == binding.EALIGN
+    assert L.laa_set_tile(h, 0) == binding.OK              # one worker per block in non-averaging steps
+    assert L.laa_set_lazy_replicas(h, 1) == binding.OK
+    assert L.laa_set_lazy_replicas(None, 1) == binding.EINVAL
+    assert L.laa_materialize(h) == binding.ENOTATTACHED
+    out = (C.c_double * 3)()
+    assert L.laa_diagnostics(h, out) == binding.ENOTATTACHED
+    assert L.laa_attach_pitched(h, C.c_void_p(16), C.c_void_p(32), C.c_void_p(48), 8, None) == binding.EINVAL  # pitch < d
     assert L.laa_attach(h, None, None, None, None) == binding.EINVAL
     assert L.laa_attach(h, C.c_void_p(2), C.c_void_p(16), C.c_void_p(16), None) == binding.EALIGN
     t, s = C.c_int64(-1), C.c_int32(-1)
