@@ -36,12 +36,14 @@ def parse():
                    help="per-worker optimum offsets: regenerated in-kernel, read from HBM, or absent")
     p.add_argument("--row-distance", type=int, default=0,
                    help="elements between the arrays of the spread layout (default workloads.SPREAD_ROW_DISTANCE)")
+    p.add_argument("--hold-gaps", action="store_true",
+                   help="spread layout as one ordinary allocation that includes the gaps (instead of laa_spread_alloc)")
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
     p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
     p.add_argument("--layout", default="auto", choices=["auto", "spread", "packed"],
-                   help="spread: all arrays of the quadratic workload 6 GB apart in one backing allocation "
-                        "(binding.spread_buffers); packed: separate dense tensors; auto: spread for c5")
+                   help="spread: the arrays of the quadratic workload 10 GB apart (binding.spread_buffers); "
+                        "packed: separate dense tensors; auto: spread for c5")
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -140,8 +142,8 @@ def main():
     if c.kind == "quadratic":
         if spread:
             rd = max(args.row_distance or wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
-            backing, bx, bacc, bsnap, a, xs = B.spread_buffers(d, W, rd, dev)
-            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rd)
+            backing, bx, bacc, bsnap, a, xs, rp = B.spread_buffers(d, W, rd, dev, hold_gaps=args.hold_gaps)
+            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rp)
             a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
             xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
         else:

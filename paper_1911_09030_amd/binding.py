@@ -24,7 +24,7 @@ EXPORTS = [
     "laa_set_tile", "laa_set_lazy_replicas", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
-    "laa_debug_philox", "laa_debug_copy",
+    "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
 ]
 
 _lib = None
@@ -73,6 +73,8 @@ def lib():
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
         "laa_diagnostics": [vp, C.POINTER(C.c_double)],
         "laa_bytes_moved": [vp, C.POINTER(u64)],
+        "laa_spread_alloc": [i32, i64, i64, C.POINTER(vp), C.POINTER(i64)],
+        "laa_spread_free": [vp],
         "laa_debug_philox": [vp, vp, vp],
         "laa_debug_copy": [vp, vp, i64, vp],
     }
@@ -99,24 +101,67 @@ def _dev_ptr(t, dtype=None):
     return C.c_void_p(t.data_ptr())
 
 
-def spread_buffers(d, W, row_distance, device="cuda:0"):
-    """One backing allocation with the 2W + 3 arrays of a dense quadratic workload placed ``row_distance``
-    elements apart: x rows, then acc rows, then snap, a, xstar.  Returns (backing, x, acc, snap, a, xstar), the
-    state arrays as [W][d] / [d] views (row pitch ``row_distance``).
+class _DeviceArray:
+    """A strided view of device memory that PyTorch can adopt through the CUDA array interface."""
+
+    def __init__(self, ptr, shape, strides_bytes, owner):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": "<f4", "data": (int(ptr), False),
+                                         "version": 3, "strides": tuple(strides_bytes)}
+        self._owner = owner
+
+
+class SpreadAllocation:
+    """Device memory from laa_spread_alloc; freed when the last reference goes away (or by close())."""
+
+    def __init__(self, n_arrays, array_bytes, distance_bytes):
+        base, dist = C.c_void_p(), C.c_int64()
+        _check(lib().laa_spread_alloc(int(n_arrays), int(array_bytes), int(distance_bytes), C.byref(base), C.byref(dist)))
+        self.base, self.distance_bytes, self.n_arrays = base.value, dist.value, int(n_arrays)
+
+    def close(self):
+        if getattr(self, "base", None):
+            lib().laa_spread_free(C.c_void_p(self.base))
+            self.base = None
+
+    __del__ = close
+
+
+def spread_buffers(d, W, row_distance, device="cuda:0", hold_gaps=False):
+    """The 2W + 3 arrays of a dense quadratic workload placed ``row_distance`` elements apart: x rows, then acc
+    rows, then snap, a, xstar.  Returns (backing, x, acc, snap, a, xstar, pitch): the state arrays as [W][d] / [d]
+    tensors with row pitch ``pitch`` (>= row_distance, rounded to the mapping granularity); keep ``backing`` alive
+    as long as the tensors are used.
 
     Why: on MI355X a thread's 2W read-modify-write streams run 6-8 % faster when the arrays streamed together
     span most of the HBM address range (d = 4e8, W = 8: 8.72 ms per step with the arrays 10 GB apart against
     9.1-9.5 ms when packed into 30 GB; the threshold scales as 1/(number of streams), as if a third of the
-    address range maps to one rank of the 12-high stacks).  The gaps are allocated but never touched."""
+    address range maps to one rank of the 12-high stacks).
+
+    Default: laa_spread_alloc, which maps only the arrays themselves (the address range between them is
+    reserved but unmapped, so it costs no device memory; never touch it).  hold_gaps=True: one ordinary
+    PyTorch allocation of (2W + 3) * row_distance elements, gaps included."""
     import torch
     d, W, rd = int(d), int(W), int(row_distance)
     if rd < d or rd % 4:
         raise ValueError("row_distance must be >= d and a multiple of 4")
-    backing = torch.empty((2 * W + 3) * rd, dtype=torch.float32, device=device)
-    x = backing[:W * rd].view(W, rd)[:, :d]
-    acc = backing[W * rd:2 * W * rd].view(W, rd)[:, :d]
-    snap, a, xstar = (backing[(2 * W + i) * rd:(2 * W + i) * rd + d] for i in range(3))
-    return backing, x, acc, snap, a, xstar
+    n = 2 * W + 3
+    if hold_gaps:
+        backing = torch.empty(n * rd, dtype=torch.float32, device=device)
+        x = backing[:W * rd].view(W, rd)[:, :d]
+        acc = backing[W * rd:2 * W * rd].view(W, rd)[:, :d]
+        snap, a, xstar = (backing[(2 * W + i) * rd:(2 * W + i) * rd + d] for i in range(3))
+        return backing, x, acc, snap, a, xstar, rd
+    backing = SpreadAllocation(n, d * 4, rd * 4)
+    db, base = backing.distance_bytes, backing.base
+    pitch = db // 4
+
+    def adopt(first, rows):
+        shape, strides = ((rows, d), (db, 4)) if rows else ((d,), (4,))
+        return torch.as_tensor(_DeviceArray(base + first * db, shape, strides, backing), device=device)
+
+    x, acc = adopt(0, W), adopt(W, W)
+    snap, a, xstar = adopt(2 * W, 0), adopt(2 * W + 1, 0), adopt(2 * W + 2, 0)
+    return backing, x, acc, snap, a, xstar, pitch
 
 
 class LocalAdaAlter:

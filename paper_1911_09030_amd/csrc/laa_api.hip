@@ -8,7 +8,10 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
+#include <vector>
 
 struct laa_ctx {
     int64_t d = 0, pitch = 0;
@@ -512,6 +515,100 @@ int laa_bytes_moved(laa_handle h, uint64_t *algorithmic_bytes)
     if (!h || !algorithmic_bytes) return fail(LAA_EINVAL, "null argument");
     *algorithmic_bytes = h->bytes;
     return LAA_OK;
+}
+
+// ---- spread allocation -------------------------------------------------------------------------------------
+namespace {
+struct SpreadAlloc {
+    size_t chunk = 0, dist = 0;
+    std::vector<hipMemGenericAllocationHandle_t> handles;
+    size_t mapped = 0;          // how many chunks are mapped
+    bool reserved = false;
+};
+std::mutex g_spread_mutex;
+std::map<void *, SpreadAlloc> g_spread;
+
+void spread_release(void *base, SpreadAlloc &sa)
+{
+    for (size_t i = 0; i < sa.mapped; ++i) (void)hipMemUnmap(static_cast<char *>(base) + i * sa.dist, sa.chunk);
+    for (auto h : sa.handles) (void)hipMemRelease(h);
+    if (sa.reserved) (void)hipMemAddressFree(base, sa.dist * sa.handles.size());
+}
+}  // namespace
+
+int laa_spread_alloc(int32_t n_arrays, int64_t array_bytes, int64_t distance_bytes, void **base,
+                     int64_t *actual_distance_bytes)
+{
+    if (!base) return fail(LAA_EINVAL, "null base");
+    *base = nullptr;
+    if (n_arrays <= 0 || array_bytes <= 0 || distance_bytes < array_bytes)
+        return fail(LAA_EINVAL, "need n_arrays > 0 and 0 < array_bytes <= distance_bytes");
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(LAA_ENODEVICE, "no HIP device available");
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = dev;
+    size_t gran = 0;
+    if ((e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityRecommended)) != hipSuccess)
+        return hip_fail(e, "hipMemGetAllocationGranularity");
+    if (gran < (size_t(2) << 20)) gran = size_t(2) << 20;      // 2 MiB blocks so that large pages can be used
+    SpreadAlloc sa;
+    sa.chunk = ((size_t)array_bytes + gran - 1) / gran * gran;
+    sa.dist = ((size_t)distance_bytes + gran - 1) / gran * gran;
+    // Physical placement: the driver hands out device memory in creation order, so a spacer created between two
+    // arrays pushes them apart; the spacers are released again before returning.
+    std::vector<hipMemGenericAllocationHandle_t> spacers;
+    for (int32_t i = 0; i < n_arrays && e == hipSuccess; ++i) {
+        hipMemGenericAllocationHandle_t h;
+        if ((e = hipMemCreate(&h, sa.chunk, &prop, 0)) != hipSuccess) break;
+        sa.handles.push_back(h);
+        if (i + 1 < n_arrays && sa.dist > sa.chunk) {
+            if ((e = hipMemCreate(&h, sa.dist - sa.chunk, &prop, 0)) != hipSuccess) break;
+            spacers.push_back(h);
+        }
+    }
+    for (auto h : spacers) (void)hipMemRelease(h);
+    void *va = nullptr;
+    if (e == hipSuccess && (e = hipMemAddressReserve(&va, sa.dist * (size_t)n_arrays, 0, nullptr, 0)) == hipSuccess)
+        sa.reserved = true;
+    hipMemAccessDesc access = {};
+    access.location = prop.location;
+    access.flags = hipMemAccessFlagsProtReadWrite;
+    for (size_t i = 0; e == hipSuccess && i < sa.handles.size(); ++i) {
+        char *p = static_cast<char *>(va) + i * sa.dist;
+        if ((e = hipMemMap(p, sa.chunk, 0, sa.handles[i], 0)) != hipSuccess) break;
+        sa.mapped = i + 1;
+        e = hipMemSetAccess(p, sa.chunk, &access, 1);
+    }
+    if (e != hipSuccess) {
+        spread_release(va, sa);
+        return hip_fail(e, "spread allocation (HIP virtual memory management)");
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_spread_mutex);
+        g_spread[va] = sa;
+    }
+    *base = va;
+    if (actual_distance_bytes) *actual_distance_bytes = (int64_t)sa.dist;
+    return LAA_OK;
+}
+
+int laa_spread_free(void *base)
+{
+    if (!base) return LAA_OK;
+    SpreadAlloc sa;
+    {
+        std::lock_guard<std::mutex> lock(g_spread_mutex);
+        auto it = g_spread.find(base);
+        if (it == g_spread.end()) return fail(LAA_EINVAL, "not a pointer returned by laa_spread_alloc");
+        sa = it->second;
+        g_spread.erase(it);
+    }
+    hipError_t e = hipDeviceSynchronize();
+    spread_release(base, sa);
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "hipDeviceSynchronize before freeing a spread allocation");
 }
 
 int laa_debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t *out)

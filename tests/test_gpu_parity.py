@@ -148,28 +148,40 @@ def test_pitched_rows(B, W, d, pitch):
             g.step_dense(dev(np.zeros((W, d), np.float32)))
 
 
-def test_spread_buffers_layout(B):
-    """binding.spread_buffers: 2W + 3 arrays a fixed distance apart in one allocation, usable as the state."""
+@pytest.mark.parametrize("hold_gaps", [False, True])
+def test_spread_buffers_layout(B, hold_gaps):
+    """binding.spread_buffers: 2W + 3 arrays a fixed distance apart, usable as the state; with hold_gaps the
+    gaps are part of one ordinary allocation, otherwise only the arrays are mapped (laa_spread_alloc)."""
     import torch
     W, d, rd, H = 4, 4 * 300, 4 * 1000, 2
-    backing, x, acc, snap, a, xs = B.spread_buffers(d, W, rd)
-    assert backing.numel() == (2 * W + 3) * rd and x.shape == (W, d) and x.stride(0) == rd
-    base = backing.data_ptr()
-    assert [t.data_ptr() - base for t in (x, acc, snap, a, xs)] == [0, 4 * W * rd, 8 * W * rd, 4 * (2 * W + 1) * rd,
-                                                                   4 * (2 * W + 2) * rd]
-    backing.fill_(7.0)
+    free0 = torch.cuda.mem_get_info()[0]
+    backing, x, acc, snap, a, xs, pitch = B.spread_buffers(d, W, rd, hold_gaps=hold_gaps)
+    assert x.shape == (W, d) and x.stride(0) == pitch and acc.stride(0) == pitch and pitch >= rd
+    assert [t.data_ptr() - x.data_ptr() for t in (acc, snap, a, xs)] == [4 * pitch * k for k in (W, 2 * W, 2 * W + 1, 2 * W + 2)]
+    if hold_gaps:
+        assert pitch == rd and backing.numel() == (2 * W + 3) * rd
+        backing.fill_(7.0)
+    else:
+        assert pitch * 4 % (2 << 20) == 0 and backing.n_arrays == 2 * W + 3
     rng = np.random.default_rng(31)
     an = rng.uniform(0.1, 10, d).astype(np.float32); xn = rng.standard_normal(d).astype(np.float32)
     a.copy_(torch.from_numpy(an)); xs.copy_(torch.from_numpy(xn))
-    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0, x=x, acc=acc, snap=snap, pitch=rd); g.set_lazy_replicas(True); g.init_state()
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0, x=x, acc=acc, snap=snap, pitch=pitch); g.set_lazy_replicas(True); g.init_state()
     g.set_generator(B.GEN_QUADRATIC, 1, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
     o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
     o.set_generator(oracle.GEN_QUADRATIC, 1, an, xn, None, oracle.OFF_PHILOX, 0.1, 0.1)
     for _ in range(2 * H + 1):
         o.step_gen(); g.step_gen()
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="spread buffers")
-    full = backing.view(2 * W + 3, rd)
-    assert bool((full[:, d:] == 7.0).all()), "the gaps between the arrays were written"
+    if hold_gaps:
+        full = backing.view(2 * W + 3, rd)
+        assert bool((full[:, d:] == 7.0).all()), "the gaps between the arrays were written"
+    else:
+        del g, x, acc, snap, a, xs
+        backing.close()
+        assert backing.base is None
+        with pytest.raises(B.LaaError):
+            B._check(B.lib().laa_spread_free(B.C.c_void_p(12345 << 21)))       # not one of ours
     with pytest.raises(ValueError):
         B.spread_buffers(d, W, d - 4)
 
@@ -512,8 +524,9 @@ def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
     if bench_layout:
         import torch
         rd = max(wl.SPREAD_ROW_DISTANCE, c.d)
-        backing, bx, bacc, bsnap, da, dxs = B.spread_buffers(c.d, c.W, rd)
-        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rd)
+        backing, bx, bacc, bsnap, da, dxs, rp = B.spread_buffers(c.d, c.W, rd)
+        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rp)
+        g._keep_backing = backing
         g.set_lazy_replicas(True)
         da.copy_(torch.from_numpy(a)); dxs.copy_(torch.from_numpy(xs))
     else:
