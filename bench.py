@@ -142,7 +142,12 @@ def main():
     if c.kind == "quadratic":
         if spread:
             rd = max(args.row_distance or wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
-            backing, bx, bacc, bsnap, a, xs, rp = B.spread_buffers(d, W, rd, dev, hold_gaps=args.hold_gaps)
+            try:
+                backing, bx, bacc, bsnap, a, xs, rp = B.spread_buffers(d, W, rd, dev, hold_gaps=args.hold_gaps)
+            except (B.LaaError, RuntimeError) as e:     # no address space / memory for it: packed tensors instead
+                print(f"bench.py: spread layout unavailable ({e}); using the packed layout", file=sys.stderr)
+                spread = False
+        if spread:
             g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rp)
             a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
             xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
