@@ -41,9 +41,9 @@ def parse():
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
     p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
-    p.add_argument("--layout", default="auto", choices=["auto", "spread", "packed"],
-                   help="spread: the arrays of the quadratic workload 10 GB apart (binding.spread_buffers); "
-                        "packed: separate dense tensors; auto: spread for c5")
+    p.add_argument("--layout", default="spread", choices=["spread", "packed"],
+                   help="spread: all [W][d] rows and [d] vectors up to 10 GB apart over the HBM address range "
+                        "(binding.spread_arrays); packed: ordinary dense tensors")
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -137,28 +137,36 @@ def main():
     d, W = c.d, c.W
 
     pitch = args.pitch or None
-    spread = c.kind == "quadratic" and (args.layout == "spread" or (args.layout == "auto" and c.name == "c5"))
-    extra = []          # further state machines stepped in the same iteration (c4's dense blocks)
-    if c.kind == "quadratic":
+    spread = args.layout != "packed"
+    keep, layouts = [], []
+
+    def alloc(dd, n_mat, n_vec):
+        """n_mat arrays [W][dd] and n_vec arrays [dd]: spread over the address range, else ordinary tensors."""
         if spread:
-            rd = max(args.row_distance or wl.SPREAD_ROW_DISTANCE, (d + 3) // 4 * 4)
             try:
-                backing, bx, bacc, bsnap, a, xs, rp = B.spread_buffers(d, W, rd, dev, hold_gaps=args.hold_gaps)
-            except (B.LaaError, RuntimeError) as e:     # no address space / memory for it: packed tensors instead
-                print(f"bench.py: spread layout unavailable ({e}); using the packed layout", file=sys.stderr)
-                spread = False
-        if spread:
-            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rp)
-            a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
-            xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
-        else:
-            g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
-            a = torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)).to(dev)
-            xs = torch.from_numpy(wl.optimum(d, c.seed)).to(dev)
+                backing, mats, vecs, rp = B.spread_arrays(dd, W, n_mat, n_vec, args.row_distance or wl.SPREAD_ROW_DISTANCE,
+                                                          dev, hold_gaps=args.hold_gaps)
+                keep.append(backing)
+                layouts.append(f"spread({rp})")
+                return mats, vecs, rp
+            except (B.LaaError, RuntimeError, ValueError) as e:   # no memory / address space for it
+                print(f"bench.py: spread layout unavailable for d={dd} ({e}); packed tensors instead", file=sys.stderr)
+        rp = pitch or dd
+        layouts.append(f"packed({rp})")
+        mats = [torch.empty((W, rp), dtype=torch.float32, device=dev)[:, :dd] for _ in range(n_mat)]
+        vecs = [torch.empty(dd, dtype=torch.float32, device=dev) for _ in range(n_vec)]
+        return mats, vecs, rp
+
+    if c.kind == "quadratic":
+        with_off = args.offsets == "array"
+        mats, (bsnap, a, xs), rp = alloc(d, 3 if with_off else 2, 3)
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
+        a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
+        xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
         g.init_state()
         off = None
-        if args.offsets == "array":
-            off = g.rows()
+        if with_off:
+            off = mats[2]
             for w in range(W):      # inputs only: N(0, off_scale^2) drawn on the device, one worker row at a time
                 off[w].normal_(0.0, c.off_scale)
         om = {"philox": B.OFF_PHILOX, "array": B.OFF_ARRAY, "none": B.OFF_NONE}[args.offsets]
@@ -175,12 +183,13 @@ def main():
                 g.step_gen()
         updates_per_step = W * d
     elif c.kind == "explicit":
-        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
-        g.init_state()
-        sig = torch.from_numpy(wl.sigma(d, c.seed)).to(dev)
-        g.set_generator(B.GEN_NOISE, c.seed, sig)
         P = 4
-        pool = [g.rows() for _ in range(P)]
+        mats, (bsnap, sig), rp = alloc(d, 2 + P, 2)
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
+        g.init_state()
+        sig.copy_(torch.from_numpy(wl.sigma(d, c.seed)))
+        g.set_generator(B.GEN_NOISE, c.seed, sig)
+        pool = mats[2:]
         for p in range(P):           # precompute the gradient pool in HBM; the timed loop streams it
             g.generate_gradient(pool[p])
             g.step_dense(pool[p])    # advance t so each pool entry uses another iteration's noise
@@ -192,7 +201,8 @@ def main():
             g.step_dense(pool[t % P])
         updates_per_step = W * d
     else:  # embedding table with row-sparse gradients + dense LSTM blocks
-        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, pitch=pitch)
+        mats, (bsnap,), rp = alloc(d, 2, 1)
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
         g.init_state()
         zipf = wl.ZipfRows(c.rows, c.zipf_s)
         P = 16
@@ -200,11 +210,11 @@ def main():
                     for t in range(P)]
         vals_pool = [torch.randn((W, c.k, c.row_len), dtype=torch.float32, device=dev) * c.val_sigma for _ in range(4)]
         dd = sum(r * q for r, q in c.dense_blocks)
-        gd = B.LocalAdaAlter(dd, W, H, c.eta, c.eps)
+        dmats, (dsnap, sigd), drp = alloc(dd, 2, 2)
+        gd = B.LocalAdaAlter(dd, W, H, c.eta, c.eps, x=dmats[0], acc=dmats[1], snap=dsnap, pitch=drp)
         gd.init_state()
-        sigd = torch.from_numpy(wl.sigma(dd, c.seed)).to(dev)
+        sigd.copy_(torch.from_numpy(wl.sigma(dd, c.seed)))
         gd.set_generator(B.GEN_NOISE, c.seed, sigd)
-        extra.append(gd)
         step_bytes = W * c.k * (c.row_len * 24 + 4)
         kernel_tag = f"sparse_step_kernel_{c.name}"
 
@@ -221,6 +231,8 @@ def main():
     lazy = not args.no_lazy_replicas and c.kind != "embedding"
     if lazy:
         g.set_lazy_replicas(True)
+    if not args.no_lazy_replicas and c.kind == "embedding":
+        gd.set_lazy_replicas(True)       # the dense blocks; the table's sparse sync never collapses
 
     # warm-up (untimed), then realign to a period boundary so the timed region holds K/H syncs
     t = 0
@@ -272,8 +284,7 @@ def main():
         "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
-                               f"lazy_replicas={'on' if lazy else 'off'} layout={'spread' if spread else 'packed'} "
-                               f"row_pitch={g.pitch}",
+                               f"lazy_replicas={'on' if lazy else 'off'} layout={'+'.join(layouts)}",
                    "syncs_in_timed_region": len(sync_it),
                    "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
                    "ms_post_sync_iteration": (sum(post_sync) / len(post_sync)) if post_sync else None,
