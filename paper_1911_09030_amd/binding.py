@@ -145,7 +145,7 @@ def spread_arrays(d, W, n_matrices, n_vectors, row_distance, device="cuda:0", ho
     n = W * int(n_matrices) + int(n_vectors)
     free = torch.cuda.mem_get_info(device)[0]
     rd = min(rd, int(0.9 * free / n) // 4)
-    rd -= rd % (1 << 19)                                   # whole 2 MiB blocks
+    rd -= rd % 4
     if rd < d:
         raise ValueError(f"{n} arrays of {d} elements cannot be spread over {free / 1e9:.0f} GB of free memory")
     if hold_gaps:
