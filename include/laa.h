@@ -173,6 +173,13 @@ int laa_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t
  * the stream).  Any pointer may be null. */
 int laa_get_counters(laa_handle h, int64_t *t, int32_t *steps_since_sync, int64_t *bad_indices);
 
+/* Resume from a checkpoint: the caller restores x, acc, snap itself (they are its arrays; call
+ * laa_materialize before saving them when lazy replicas are on) and then sets the iteration count
+ * and the number of local steps since the last sync that laa_get_counters reported.  The generator
+ * continues with the same random numbers as an uninterrupted run.  The next laa_sync averages the
+ * whole table even if only sparse steps follow (the rows touched before the checkpoint are unknown). */
+int laa_set_counters(laa_handle h, int64_t t, int32_t steps_since_sync);
+
 /* Rows touched by sparse steps since the last sync, ascending, into out (HOST,
  * capacity cap); *n receives the total count even if it exceeds cap.
  * Synchronises the stream. */

@@ -457,6 +457,18 @@ int laa_get_counters(laa_handle h, int64_t *t, int32_t *steps_since_sync, int64_
     return LAA_OK;
 }
 
+int laa_set_counters(laa_handle h, int64_t t, int32_t steps_since_sync)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (t < 0 || steps_since_sync < 0 || steps_since_sync > h->H || steps_since_sync > t)
+        return fail(LAA_EINVAL, "need 0 <= steps_since_sync <= min(H, t)");
+    h->t = t;
+    h->s = steps_since_sync;
+    h->collapsed = false;                 // the caller has put full arrays in place
+    h->sparse_only_since_sync = false;    // rows touched before the checkpoint are unknown: next sync is dense
+    return h->attached ? clear_dirty(h) : LAA_OK;
+}
+
 int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n)
 {
     int rc = check_ready(h);
