@@ -139,6 +139,15 @@ int laa_local_step_dense(laa_handle h, const float *grads);
 int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a, const float *xstar,
                       const float *off, int32_t off_mode, float noise_scale, float off_scale);
 
+/* This handle holds a shard of a larger problem: its column j is global column first_column + j
+ * (first_column a multiple of 4, so that the four normals of one Philox block stay together) and its
+ * worker w is global worker first_worker + w.  The generator's counters use the global indices, so
+ * a run split by columns (each shard with all W workers; nothing is exchanged) or by workers (one
+ * worker or a few per shard, the deployment of Algorithm 3; the local steps need no exchange and the
+ * Synchronize step becomes an all-reduce outside this library) draws the random numbers of the unsplit
+ * run.  Default 0, 0.  Explicit-gradient and sparse steps are not affected. */
+int laa_set_shard(laa_handle h, int64_t first_column, int32_t first_worker);
+
 /* One local step with the gradient generated in the kernel at iteration t+1. */
 int laa_local_step_gen(laa_handle h);
 

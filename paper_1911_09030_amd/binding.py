@@ -23,7 +23,7 @@ EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
     "laa_set_tile", "laa_set_lazy_replicas", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
-    "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
+    "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_set_shard", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
     "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
 ]
 
@@ -71,6 +71,7 @@ def lib():
         "laa_step_sparse": [vp, vp, vp, i32, i32],
         "laa_get_counters": [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)],
         "laa_set_counters": [vp, i64, i32],
+        "laa_set_shard": [vp, i64, i32],
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
         "laa_diagnostics": [vp, C.POINTER(C.c_double)],
         "laa_bytes_moved": [vp, C.POINTER(u64)],
@@ -295,6 +296,9 @@ class LocalAdaAlter:
         t, s, bad = C.c_int64(), C.c_int32(), C.c_int64()
         _check(self.L.laa_get_counters(self.h, C.byref(t), C.byref(s), C.byref(bad) if with_bad else None))
         return (t.value, s.value, bad.value) if with_bad else (t.value, s.value)
+
+    def set_shard(self, first_column=0, first_worker=0):
+        _check(self.L.laa_set_shard(self.h, int(first_column), int(first_worker)))
 
     def set_counters(self, t, steps_since_sync):
         _check(self.L.laa_set_counters(self.h, int(t), int(steps_since_sync)))

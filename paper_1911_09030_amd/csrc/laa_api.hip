@@ -31,6 +31,8 @@ struct laa_ctx {
     // generator
     int32_t gen_mode = 0, off_mode = 0;
     uint64_t seed = 0;
+    int64_t col0 = 0;                 // global indices of column 0 and worker 0 (generator counters)
+    int32_t w0 = 0;
     const float *a = nullptr, *xstar = nullptr, *off = nullptr;
     float noise_scale = 0, off_scale = 0;
     // sparse bookkeeping (library-owned device memory)
@@ -168,6 +170,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.pad = (float)(h->s + 1) * eps2;                      // t' eps^2, t' = steps since sync + 1
     a.noise_scale = h->noise_scale; a.off_scale = h->off_scale;
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.col0 = h->col0; a.w0 = h->w0;
     a.t_lo = (uint32_t)(h->t + 1);
     a.grad_source = kind == STEP_DENSE ? laa::GRAD_EXPLICIT : h->gen_mode;
     a.off_source = kind == STEP_DENSE ? laa::OFFSET_NONE : h->off_mode;
@@ -178,7 +181,6 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.wt = h->wt;
     a.split = h->split;
     a.vec4 = h->vec4 && (kind == STEP_DENSE ? aligned(grads, 16) : h->gen_aligned16);
-    if (!a.vec4) a.wt = 1;
 
     hipError_t e = laa::launch_step(a, h->stream);
     if (e != hipSuccess) return hip_fail(e, "step kernel launch");
@@ -346,6 +348,17 @@ int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a,
     return LAA_OK;
 }
 
+int laa_set_shard(laa_handle h, int64_t first_column, int32_t first_worker)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    if (first_column < 0 || first_column % 4 != 0)
+        return fail(LAA_EINVAL, "first_column must be a non-negative multiple of 4 (got %lld)", (long long)first_column);
+    if (first_column > INT64_MAX - h->d) return fail(LAA_EINVAL, "first_column + d overflows");
+    if (first_worker < 0 || first_worker > INT32_MAX - h->W) return fail(LAA_EINVAL, "bad first_worker %d", first_worker);
+    h->col0 = first_column; h->w0 = first_worker;
+    return LAA_OK;
+}
+
 int laa_local_step_dense(laa_handle h, const float *grads) { return dense_step(h, STEP_DENSE, grads, false); }
 int laa_local_step_gen(laa_handle h) { return dense_step(h, STEP_GEN, nullptr, false); }
 int laa_step_dense(laa_handle h, const float *grads) { return dense_step(h, STEP_DENSE, grads, true); }
@@ -365,11 +378,12 @@ int laa_generate_gradient(laa_handle h, float *out)
     a.d = h->d; a.pitch = h->pitch; a.W = h->W;
     a.noise_scale = h->noise_scale; a.off_scale = h->off_scale;
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.col0 = h->col0; a.w0 = h->w0;
     a.t_lo = (uint32_t)(h->t + 1);
     a.grad_source = h->gen_mode; a.off_source = h->off_mode;
     a.collapsed_in = h->collapsed;
     a.vec4 = h->vec4 && h->gen_aligned16 && aligned(out, 16);
-    a.wt = a.vec4 ? h->wt : 1;
+    a.wt = h->wt;
     hipError_t e = laa::launch_step(a, h->stream);
     return e == hipSuccess ? LAA_OK : hip_fail(e, "gradient kernel launch");
 }
@@ -421,7 +435,7 @@ int laa_sync(laa_handle h)
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
         const bool collapse = h->lazy && !x_only;
-        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->vec4 ? h->wt : 1, x_only,
+        e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->wt, x_only,
                              collapse, h->stream);
         if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
         h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
@@ -510,6 +524,7 @@ int laa_diagnostics(laa_handle h, double *out)
     a.d = h->d; a.pitch = h->pitch; a.W = h->W;
     a.off_scale = h->off_scale;
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.col0 = h->col0; a.w0 = h->w0;
     a.off_source = h->off_mode;
     a.collapsed_in = h->collapsed;
     a.vec4 = h->vec4 && h->gen_aligned16;

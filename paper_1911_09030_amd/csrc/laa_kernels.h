@@ -27,6 +27,8 @@ struct StepArgs {
     float eps2;
     float noise_scale, off_scale;
     uint32_t seed_lo, seed_hi;
+    int64_t col0;        // global index of column 0 (multiple of 4) and
+    int32_t w0;          // global index of worker 0: the generator's counters are global
     uint32_t t_lo;       // iteration number of this step (low 32 bits), Philox counter word
     int32_t grad_source, off_source;
     bool sync;           // average over the worker axis in the same pass

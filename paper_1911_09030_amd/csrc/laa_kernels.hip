@@ -147,9 +147,10 @@ __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int6
     if constexpr (GS == GRAD_EXPLICIT) {
         g = ld<VEC, NT_LD>(a.grads + row);
     } else {
-        const uint64_t qa = (uint64_t)j >> 2;
+        const uint64_t qa = (uint64_t)(j + a.col0) >> 2;      // col0 % 4 == 0: j & 3 is the global lane too
+        const uint32_t wg = (uint32_t)(w + a.w0);
         float n[4];
-        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, (uint32_t)w, a.t_lo, n);
+        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, wg, a.t_lo, n);
         if constexpr (GS == GRAD_NOISE) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) g.v[e] = av.v[e] * n[VEC == 4 ? e : (int)(j & 3)];
@@ -159,7 +160,7 @@ __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int6
                 o = ld<VEC, NT_LD>(a.off + row);
             } else if constexpr (OS == OFFSET_PHILOX) {
                 float m[4];
-                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, (uint32_t)w, 0u, m);
+                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, wg, 0u, m);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) o.v[e] = a.off_scale * m[VEC == 4 ? e : (int)(j & 3)];
             } else {
@@ -639,7 +640,7 @@ __global__ __launch_bounds__(BLOCK) void diag_kernel(const StepArgs a, double *_
                 for (int e = 0; e < VEC; ++e) moff.v[e] += o.v[e];
             } else if constexpr (OS == OFFSET_PHILOX) {
                 float m[4];
-                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, (uint64_t)j >> 2, (uint32_t)w, 0u, m);
+                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, (uint64_t)(j + a.col0) >> 2, (uint32_t)(w + a.w0), 0u, m);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) moff.v[e] += a.off_scale * m[VEC == 4 ? e : (int)(j & 3)];
             }
@@ -782,7 +783,13 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
         return hipErrorInvalidValue;
     }
     if (!dense_grid(a.d, false, a.W, &grid)) return hipErrorInvalidValue;
-    return launch_step_2<1, 1>(a, grid, s);
+    switch (a.wt) {             // same batches as the vector path: the order of the worker-axis sum, and with it
+    case 1: return launch_step_2<1, 1>(a, grid, s);       // every bit of the result, does not depend on alignment
+    case 2: return launch_step_2<1, 2>(a, grid, s);
+    case 4: return launch_step_2<1, 4>(a, grid, s);
+    case 8: return launch_step_2<1, 8>(a, grid, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 template <int VEC, int WT>
@@ -812,7 +819,13 @@ hipError_t launch_mean(float *x, float *acc, float *snap, int64_t d, int64_t pit
         return hipErrorInvalidValue;
     }
     if (!dense_grid(d, false, W, &grid)) return hipErrorInvalidValue;
-    return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+    switch (wt) {
+    case 1: return launch_mean_2<1, 1>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+    case 2: return launch_mean_2<1, 2>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+    case 4: return launch_mean_2<1, 4>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+    case 8: return launch_mean_2<1, 8>(x, acc, snap, d, pitch, W, x_only, collapse, grid, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,

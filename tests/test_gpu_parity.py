@@ -424,6 +424,93 @@ def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d, tile):
         parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, bar, floor_x=1.0, what=f"gen t={t}")
 
 
+@pytest.mark.parametrize("d,split", [(4 * 64 * 11, 4 * 64 * 4), (4 * 300 + 2, 4 * 77)])
+def test_shard_by_columns_equals_the_unsplit_run(B, d, split):
+    """Two handles that hold columns [0, split) and [split, d) with laa_set_shard reproduce the unsplit run bit for
+    bit, syncs and Philox offsets included (nothing crosses the column axis)."""
+    import torch
+    W, H = 4, 3
+    rng = np.random.default_rng(53)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    full = B.LocalAdaAlter(d, W, H, 0.5, 1.0); full.init_state(dev(x0))
+    full.set_generator(B.GEN_QUADRATIC, 77, dev(a), dev(xs), None, B.OFF_PHILOX, 0.1, 0.1)
+    parts = []
+    for lo, hi in ((0, split), (split, d)):
+        p = B.LocalAdaAlter(hi - lo, W, H, 0.5, 1.0); p.init_state(dev(x0[lo:hi]))
+        p.set_shard(lo, 0)
+        p.set_generator(B.GEN_QUADRATIC, 77, dev(a[lo:hi]), dev(xs[lo:hi]), None, B.OFF_PHILOX, 0.1, 0.1)
+        parts.append(p)
+    for _ in range(2 * H + 1):
+        full.step_gen()
+        for p in parts:
+            p.step_gen()
+    torch.cuda.synchronize()
+    for name in ("x", "acc", "snap"):
+        whole = getattr(full, name)
+        glued = torch.cat([getattr(p, name) for p in parts], dim=-1)
+        assert torch.equal(whole, glued), name
+    df = full.diagnostics()
+    dp = [p.diagnostics() for p in parts]
+    assert np.allclose(df, np.sum(dp, axis=0), rtol=1e-12, atol=0)      # the three diagnostics are sums over columns
+
+
+def test_shard_by_workers_local_steps_equal_the_unsplit_run(B):
+    """One or two workers per handle (the deployment of Algorithm 3): their local steps draw the global worker's random
+    numbers; averaging the shards' rows by hand gives the unsplit run's Synchronize."""
+    import torch
+    W, H, d = 4, 3, D_SMALL
+    rng = np.random.default_rng(59)
+    a = dev(rng.uniform(0.1, 10, d).astype(np.float32)); xs = dev(rng.standard_normal(d).astype(np.float32))
+    full = B.LocalAdaAlter(d, W, H, 0.5, 1.0); full.init_state()
+    full.set_generator(B.GEN_QUADRATIC, 78, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    parts = []
+    for w0, wn in ((0, 1), (1, 2), (3, 1)):
+        p = B.LocalAdaAlter(d, wn, H, 0.5, 1.0); p.init_state()
+        p.set_shard(0, w0)
+        p.set_generator(B.GEN_QUADRATIC, 78, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+        parts.append(p)
+    for _ in range(H):
+        full.local_step_gen()
+        for p in parts:
+            p.local_step_gen()
+    torch.cuda.synchronize()
+    px = torch.cat([p.x for p in parts]); pa = torch.cat([p.acc for p in parts])
+    assert torch.equal(full.x, px) and torch.equal(full.acc, pa)
+    full.sync()
+    torch.cuda.synchronize()
+    # the all-reduce a deployment would run: same balanced order as the kernel's register tree for W = 4
+    mx = ((px[0] + px[1]) + (px[2] + px[3])) * 0.25
+    ma = ((pa[0] + pa[1]) + (pa[2] + pa[3])) * 0.25
+    assert torch.equal(full.x[0], mx) and torch.equal(full.snap, ma)
+
+
+def test_generator_counters_beyond_32_bits(B):
+    """A shard whose first column is past 2^34: the block index j/4 no longer fits the first counter word and its high
+    half goes into the stream word; the oracle follows the same global columns."""
+    import torch
+    W, H, d = 3, 2, 4 * 64 * 3 + 4
+    first = (1 << 34) - 4 * 100            # the shard straddles the point where j/4 reaches 2^32
+    rng = np.random.default_rng(61)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.set_columns(first + np.arange(d, dtype=np.int64)); o.init_state()
+    o.set_generator(oracle.GEN_QUADRATIC, 5, a, xs, None, oracle.OFF_PHILOX, 0.1, 0.1)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(); g.set_shard(first, 0)
+    g.set_generator(B.GEN_QUADRATIC, 5, dev(a), dev(xs), None, B.OFF_PHILOX, 0.1, 0.1)
+    low = B.LocalAdaAlter(d, W, H, 0.5, 1.0); low.init_state()          # same shard without the base: must differ
+    low.set_generator(B.GEN_QUADRATIC, 5, dev(a), dev(xs), None, B.OFF_PHILOX, 0.1, 0.1)
+    for t in range(1, 2 * H + 2):
+        G_ref = o.gradient(t)
+        G_gpu = host(g.generate_gradient())
+        assert np.max(np.abs(G_gpu - G_ref) / _gen_scale(a, o.x, xs, 0.1, 0.1)) <= 1e-6, t
+        if t == 1:
+            G_low = host(low.generate_gradient())
+            assert np.mean(np.abs(G_low - G_ref) > 1e-3) > 0.9
+        g.step_gen(); o.step_gen()
+    torch.cuda.synchronize()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="high columns")
+
+
 def test_generator_statistics_on_device(B):
     """The device normals themselves: moments over 4M draws (noise mode with a = 1 writes n directly)."""
     import torch
