@@ -263,7 +263,19 @@ def main():
         per_step_ms = [ev[i].elapsed_time(mid[t_first + i]) for i in range(K)]
     # the dominant kernel is the plain step: not the averaging one ((i+1) % H == 0) and, with lazy replicas, not the
     # one right after it (i % H == 0), which reads the collapsed state
-    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not (lazy and i % H == 0)] or per_step_ms
+    kernel_name = kernel_tag.rsplit("_", 1)[0]
+    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not (lazy and i % H == 0)]
+    if not plain and c.kind != "embedding":
+        # H = 1 (or H = 2 with lazy replicas): no plain step exists, the averaging step is the dominant kernel.  It
+        # reads the state (collapsed when the previous iteration averaged too), the inputs, and writes the means.
+        inputs = step_bytes // d - (16 * W + 4)
+        state_in = 8 if (lazy and H == 1) else 8 * W + 4
+        state_out = 8 if lazy else 8 * W + 4
+        step_bytes = (state_in + inputs + state_out) * d
+        kernel_tag += "_sync"
+        kernel_name += " (averaging step)"
+        plain = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
+    plain = plain or per_step_ms
     post_sync = [per_step_ms[i] for i in range(K) if lazy and i % H == 0 and (i + 1) % H != 0]
     sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
     kern_ms = sum(plain) / len(plain)
@@ -291,7 +303,7 @@ def main():
                    "method_bytes_per_element_update": 16 + 4 / W + (16 * W + 4) / (W * H)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(kernel_tag),
-                     "kernel": kernel_tag.rsplit("_", 1)[0], "kernel_ms": kern_ms,
+                     "kernel": kernel_name, "kernel_ms": kern_ms,
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     if not args.no_cpu_baseline and c.kind == "quadratic":
