@@ -47,6 +47,8 @@ def parse():
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--sparse-repeats", action="store_true",
+                   help="workload c4: draw each worker's rows independently (with repeats) and use the coalescing sparse step")
     p.add_argument("--calibrate-copy", type=int, default=0,
                    help="after the run, launch the plain copy kernel this many times over one row of d floats "
                         "(a known volume for scaling profiler byte counters)")
@@ -206,8 +208,15 @@ def main():
         g.init_state()
         zipf = wl.ZipfRows(c.rows, c.zipf_s)
         P = 16
-        idx_pool = [torch.from_numpy(wl.sparse_step(zipf, W, c.k, c.row_len, c.seed, t, with_vals=False)[0]).to(dev)
-                    for t in range(P)]
+        if args.sparse_repeats:      # tokens drawn independently: popular rows repeat within a worker's list
+            import numpy as np
+            rng = np.random.default_rng(c.seed)
+            idx_pool = [torch.from_numpy(np.minimum(np.searchsorted(zipf.cdf, rng.random((W, c.k))), c.rows - 1)
+                                         .astype(np.int32)).to(dev) for t in range(P)]
+            g.set_sparse_coalesce(True)
+        else:
+            idx_pool = [torch.from_numpy(wl.sparse_step(zipf, W, c.k, c.row_len, c.seed, t, with_vals=False)[0]).to(dev)
+                        for t in range(P)]
         vals_pool = [torch.randn((W, c.k, c.row_len), dtype=torch.float32, device=dev) * c.val_sigma for _ in range(4)]
         dd = sum(r * q for r, q in c.dense_blocks)
         dmats, (dsnap, sigd), drp = alloc(dd, 2, 2)

@@ -158,11 +158,20 @@ int laa_generate_gradient(laa_handle h, float *out);
 /* One local step with row-sparse gradients: the table is d / row_len rows of
  * row_len floats; worker w updates rows idx[w][0..k) (device int32, [W][k])
  * with values vals [W][k][row_len] (device).  Rows listed by one worker in one
- * call must be distinct (different workers may list the same row).  Rows that
+ * call must be distinct unless laa_set_sparse_coalesce is on (different workers
+ * may always list the same row).  Rows that
  * are not listed are left untouched, which is exactly Algorithm 3 with a zero
  * gradient there.  Indices outside [0, d/row_len) are skipped and counted
  * (laa_get_counters bad_indices).  row_len must be a multiple of 4. */
 int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len);
+
+/* Allow one worker to list a row several times in one sparse step (a batch of tokens with repeated
+ * words).  The row's gradient is then the sum of its entries, added in list order, and the step of
+ * Algorithm 3 is taken once with that sum (so acc grows by the square of the sum).  Each worker's list
+ * is sorted on the device first, which limits k to 8192 rows per worker and step (LAA_EINVAL beyond)
+ * and costs a small extra pass; lists without repeats give bit-identical results either way.
+ * Off by default. */
+int laa_set_sparse_coalesce(laa_handle h, int32_t on);
 
 /* Algorithm 3, Synchronize: x[w] and acc[w] become the means over w, snap the
  * mean acc.  After only sparse steps just the rows touched since the last sync

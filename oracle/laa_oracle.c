@@ -375,7 +375,11 @@ int ora_local_step_sparse(ora_ctx *c, const int32_t *idx, const real *vals, int3
         for (int32_t i = 0; i < k; ++i) {
             const int64_t r = idx[(size_t)w * k + i];
             for (int32_t e = 0; e < row_len; ++e)
+#if defined(ORA_PLANT_SPARSE_LAST_WINS)
+                c->G[(size_t)w * c->d + r * row_len + e] = vals[((size_t)w * k + i) * row_len + e];  /* planted */
+#else
                 c->G[(size_t)w * c->d + r * row_len + e] += vals[((size_t)w * k + i) * row_len + e];
+#endif
             c->dirty[r] = 1;
         }
     return ora_local_step_dense(c, c->G);

@@ -21,7 +21,7 @@ ALGO_LOCAL_ADAALTER, ALGO_DIST_ADAGRAD, ALGO_LOCAL_SGD = 0, 1, 2
 
 EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
-    "laa_set_tile", "laa_set_lazy_replicas", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
+    "laa_set_tile", "laa_set_lazy_replicas", "laa_set_sparse_coalesce", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_set_shard", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
     "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
@@ -71,6 +71,7 @@ def lib():
         "laa_step_sparse": [vp, vp, vp, i32, i32],
         "laa_get_counters": [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)],
         "laa_set_counters": [vp, i64, i32],
+        "laa_set_sparse_coalesce": [vp, i32],
         "laa_set_shard": [vp, i64, i32],
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
         "laa_diagnostics": [vp, C.POINTER(C.c_double)],
@@ -296,6 +297,9 @@ class LocalAdaAlter:
         t, s, bad = C.c_int64(), C.c_int32(), C.c_int64()
         _check(self.L.laa_get_counters(self.h, C.byref(t), C.byref(s), C.byref(bad) if with_bad else None))
         return (t.value, s.value, bad.value) if with_bad else (t.value, s.value)
+
+    def set_sparse_coalesce(self, on=True):
+        _check(self.L.laa_set_sparse_coalesce(self.h, 1 if on else 0))
 
     def set_shard(self, first_column=0, first_worker=0):
         _check(self.L.laa_set_shard(self.h, int(first_column), int(first_worker)))

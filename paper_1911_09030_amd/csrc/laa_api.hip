@@ -40,6 +40,11 @@ struct laa_ctx {
     int32_t row_len = 0;
     uint32_t *dirty = nullptr;
     int32_t *dirty_list = nullptr;
+    bool coalesce = false;            // sparse steps add up rows that a worker lists more than once
+    uint64_t *sort_keys = nullptr;    // [W][k] sorted (row, position) keys of the coalescing step
+    int64_t sort_cap = 0;             // keys allocated
+    float *partials = nullptr;        // partial sums of rows listed many times
+    int64_t partial_cap = 0;          // floats allocated
     uint32_t *dirty_count = nullptr, *scan_scratch = nullptr;
     unsigned long long *bad = nullptr;
     double *diag_scratch = nullptr;   // block partials + results of laa_diagnostics
@@ -91,6 +96,10 @@ void free_sparse(laa_ctx *h)
     if (h->dirty_count) (void)hipFree(h->dirty_count);
     if (h->scan_scratch) (void)hipFree(h->scan_scratch);
     if (h->bad) (void)hipFree(h->bad);
+    if (h->sort_keys) (void)hipFree(h->sort_keys);
+    h->sort_keys = nullptr; h->sort_cap = 0;
+    if (h->partials) (void)hipFree(h->partials);
+    h->partials = nullptr; h->partial_cap = 0;
     h->dirty = nullptr; h->dirty_list = nullptr; h->dirty_count = nullptr; h->scan_scratch = nullptr; h->bad = nullptr;
     h->n_rows = 0; h->row_len = 0;
 }
@@ -290,6 +299,13 @@ int laa_set_lazy_replicas(laa_handle h, int32_t on)
     return LAA_OK;
 }
 
+int laa_set_sparse_coalesce(laa_handle h, int32_t on)
+{
+    if (!h) return fail(LAA_EINVAL, "null handle");
+    h->coalesce = on != 0;
+    return LAA_OK;
+}
+
 int laa_materialize(laa_handle h)
 {
     int rc = check_ready(h);
@@ -403,6 +419,9 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     if (k > 0 && !aligned(idx, 4)) return fail(LAA_EALIGN, "idx not 4-byte aligned");
     if (h->s >= h->H)
         return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
+    if (h->coalesce && k > laa::coalesce_max_k())
+        return fail(LAA_EINVAL, "k = %d exceeds the coalescing step's limit of %d rows per worker and step", k,
+                    laa::coalesce_max_k());
     rc = ensure_sparse(h, row_len);
     if (rc != LAA_OK) return rc;
     if ((rc = materialize(h)) != LAA_OK) return rc;      // the row kernel reads every worker's own rows
@@ -412,8 +431,34 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     a.d = h->d; a.pitch = h->pitch; a.n_rows = h->n_rows; a.W = h->W; a.k = k; a.row_len = row_len;
     a.eta = eta_at(h, h->t + 1);
     a.pad = (float)(h->s + 1) * (float)(h->eps * h->eps);
-    hipError_t e = laa::launch_sparse_step(a, h->stream);
-    if (e != hipSuccess) return hip_fail(e, "sparse step kernel launch");
+    hipError_t e;
+    if (h->coalesce && k > 0) {
+        const int64_t need = (int64_t)h->W * k;
+        if (need > h->sort_cap) {
+            if (h->sort_keys) (void)hipFree(h->sort_keys);        // hipFree waits for the kernels that still use it
+            h->sort_keys = nullptr; h->sort_cap = 0;
+            if ((e = hipMalloc(&h->sort_keys, (size_t)need * sizeof(uint64_t))) != hipSuccess)
+                return hip_fail(e, "hipMalloc sort keys");
+            h->sort_cap = need;
+        }
+        const int64_t need_p = laa::coalesce_partial_rows(h->W, k) * row_len;
+        if (need_p > h->partial_cap) {
+            if (h->partials) (void)hipFree(h->partials);
+            h->partials = nullptr; h->partial_cap = 0;
+            if ((e = hipMalloc(&h->partials, (size_t)need_p * sizeof(float))) != hipSuccess)
+                return hip_fail(e, "hipMalloc partial rows");
+            h->partial_cap = need_p;
+        }
+        a.partials = h->partials;
+        if ((e = laa::launch_sort_rows(idx, h->sort_keys, h->W, k, h->n_rows, h->stream)) != hipSuccess)
+            return hip_fail(e, "row sort kernel launch");
+        a.keys = h->sort_keys;
+        if ((e = laa::launch_sparse_step_coalesce(a, h->stream)) != hipSuccess)
+            return hip_fail(e, "coalescing sparse step kernel launch");
+        h->bytes += (uint64_t)need * 16;                          // keys written, then read
+    } else {
+        if ((e = laa::launch_sparse_step(a, h->stream)) != hipSuccess) return hip_fail(e, "sparse step kernel launch");
+    }
     h->bytes += (uint64_t)h->W * (uint64_t)k * ((uint64_t)row_len * 24 + 4);
     h->t += 1;
     h->s += 1;

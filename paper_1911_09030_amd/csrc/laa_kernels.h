@@ -53,6 +53,8 @@ struct SparseArgs {
     float *x, *acc, *snap;
     const int32_t *idx;  // [W][k]
     const float *vals;   // [W][k][row_len]
+    const uint64_t *keys; // [W][k] sorted (row << 32 | position in the list), coalescing step only
+    float *partials;     // coalesce_partial_rows(W, k) rows of row_len floats, coalescing step only
     uint32_t *dirty;     // bitmap, one bit per row
     unsigned long long *bad; // count of skipped out-of-range indices
     int64_t d;
@@ -62,6 +64,14 @@ struct SparseArgs {
     float eta, pad;
 };
 hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s);
+// Largest k the coalescing step takes: one thread block sorts a worker's list in LDS.
+int32_t coalesce_max_k();
+// Rows of row_len floats the coalescing step needs for partial sums of long runs.
+int64_t coalesce_partial_rows(int32_t W, int32_t k);
+// Sort every worker's list by (row, position) into keys [W][k]; out-of-range rows go to the end.
+hipError_t launch_sort_rows(const int32_t *idx, uint64_t *keys, int32_t W, int32_t k, int64_t n_rows, hipStream_t s);
+// Row-sparse step on sorted lists: entries of one worker that list the same row are added up first.
+hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s);
 // bitmap -> ascending row list (device) + count (device); scratch holds one uint32 per 1024 bitmap words (+1)
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s);

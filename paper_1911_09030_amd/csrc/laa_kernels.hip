@@ -479,6 +479,160 @@ __global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
     if (lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
 }
 
+// Row-sparse step for lists in which one worker may name a row several times (a batch of tokens with repeated
+// words): the gradient of that row is the sum of its entries, and Algorithm 3 is applied once to the sum.
+// Pass 1 sorts each worker's list by (row, position) in LDS, one thread block per worker (bitonic network on
+// 64-bit keys); pass 2 gives one wavefront to every sorted position, the wavefront at the first entry of a row
+// adds the entries of the run in list order and takes the step, the others leave at once.
+static constexpr int SORT_THREADS = 1024;
+static constexpr int SORT_MAX_K = 8192;                      // 64 KiB of LDS
+static constexpr uint32_t ROW_INVALID = 0xFFFFFFFEu;         // out-of-range rows sort behind every valid row
+
+__global__ __launch_bounds__(SORT_THREADS) void sort_rows_kernel(const int32_t *__restrict__ idx,
+                                                                 uint64_t *__restrict__ keys, int32_t k, int32_t kp,
+                                                                 int64_t n_rows)
+{
+    extern __shared__ uint64_t sort_sh[];                    // kp keys, kp a power of two >= k
+    const int64_t base = (int64_t)blockIdx.x * k;
+    for (int32_t i = threadIdx.x; i < kp; i += SORT_THREADS) {
+        uint64_t key = ~0ull;                                // padding sorts last
+        if (i < k) {
+            const int32_t r = idx[base + i];
+            const uint32_t rr = (r < 0 || (int64_t)r >= n_rows) ? ROW_INVALID : (uint32_t)r;
+            key = ((uint64_t)rr << 32) | (uint32_t)i;
+        }
+        sort_sh[i] = key;
+    }
+    __syncthreads();
+    for (int32_t size = 2; size <= kp; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = threadIdx.x; t < (kp >> 1); t += SORT_THREADS) {
+                const int32_t lo = 2 * t - (t & (stride - 1));        // the pair (lo, lo + stride)
+                const int32_t hi = lo + stride;
+                const bool ascending = (lo & size) == 0;
+                const uint64_t u = sort_sh[lo], v = sort_sh[hi];
+                if ((u > v) == ascending) { sort_sh[lo] = v; sort_sh[hi] = u; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int32_t i = threadIdx.x; i < k; i += SORT_THREADS) keys[base + i] = sort_sh[i];
+}
+
+// Sorted entries that list one row form a run.  A run is cut at every SEG-th sorted position, so that a word that
+// fills a large part of the batch is added up by many wavefronts:
+//   phase 0: the wavefront at the first entry of a run, and at every position that is a multiple of SEG inside a run,
+//            adds the entries from its position to the next multiple of SEG (or the end of the run) in list order.
+//            If that is the whole run it takes the step; otherwise it stores the sum as a partial row.
+//   phase 1: the wavefront at the first entry of a run that crosses a multiple of SEG adds the partial rows in
+//            order and takes the step.
+// Partial rows: two per bucket of SEG positions (the odd one for a run that starts in the bucket, the even one for the
+// run that enters it from the left); at most one of each exists.
+static constexpr int SEG = 32;
+static constexpr int GATHER = 8;                                     // loads in flight while adding in order
+
+__device__ __forceinline__ uint32_t key_row(uint64_t key) { return (uint32_t)(key >> 32); }
+
+__device__ __forceinline__ void sparse_row_update(const SparseArgs &a, float *xr, float *br, const float *sr, int32_t e,
+                                                  const Pack<4> &g)
+{
+    const Pack<4> s = ld<4, false>(sr + e);
+    Pack<4> xv = ld<4, false>(xr + e), bv = ld<4, false>(br + e);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float step = a.eta / sqrtf(s.v[c] + a.pad);
+        xv.v[c] = fmaf(-g.v[c], step, xv.v[c]);
+        bv.v[c] = fmaf(g.v[c], g.v[c], bv.v[c]);
+    }
+    st<4, false>(xr + e, xv);
+    st<4, false>(br + e, bv);
+}
+
+template <int PHASE>
+__global__ __launch_bounds__(BLOCK) void sparse_step_coalesce_kernel(const SparseArgs a)
+{
+    const int64_t pair = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x / WAVE);
+    const int lane = threadIdx.x % WAVE;
+    if (pair >= (int64_t)a.W * a.k) return;
+    const int32_t w = (int32_t)(pair / a.k);
+    const int32_t p = (int32_t)(pair - (int64_t)w * a.k);
+    const uint64_t *kw = a.keys + (int64_t)w * a.k;
+    const uint64_t key = kw[p];
+    const uint32_t r = key_row(key);
+    if (r == ROW_INVALID) {
+        if (PHASE == 0 && lane == 0) atomicAdd(a.bad, 1ull);
+        return;
+    }
+    const bool head = p == 0 || key_row(kw[p - 1]) != r;             // first entry of its run
+    const int32_t bnd = (p / SEG + 1) * SEG;                         // next multiple of SEG
+    const bool goes_on = bnd < a.k && key_row(kw[bnd]) == r;         // sorted: then all of [p, bnd] lists r
+    const int64_t buckets = (a.k + SEG - 1) / SEG;                   // per worker
+    const int64_t bucket = (int64_t)w * buckets + p / SEG;
+    const int64_t col = (int64_t)r * a.row_len;
+    float *xr = a.x + (int64_t)w * a.pitch + col;
+    float *br = a.acc + (int64_t)w * a.pitch + col;
+    const float *sr = a.snap + col;
+    if constexpr (PHASE == 0) {
+        if (!head && p % SEG != 0) return;
+        int32_t n = 1;                                               // entries of this piece: p .. p + n - 1 < bnd
+        {
+            const int32_t q = p + 1 + lane;
+            const bool same = q < bnd && q < a.k && key_row(kw[q]) == r;
+            n += __builtin_ctzll(~__ballot(same));                   // SEG - 1 < 64: some lane is always false
+        }
+        const bool whole = head && !goes_on;
+        const float *vw = a.vals + (int64_t)w * a.k * a.row_len;
+        float *dst = a.partials + (2 * bucket + (head ? 1 : 0)) * a.row_len;
+        for (int32_t e = lane * 4; e < a.row_len; e += WAVE * 4) {
+            Pack<4> g = ld<4, true>(vw + (int64_t)(uint32_t)key * a.row_len + e);
+            for (int32_t q = 1; q < n; q += GATHER) {
+                Pack<4> v[GATHER];
+#pragma unroll
+                for (int u = 0; u < GATHER; ++u)
+                    if (q + u < n) v[u] = ld<4, true>(vw + (int64_t)(uint32_t)kw[p + q + u] * a.row_len + e);
+#pragma unroll
+                for (int u = 0; u < GATHER; ++u)
+                    if (q + u < n) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) g.v[c] += v[u].v[c];
+                    }
+            }
+            if (whole) sparse_row_update(a, xr, br, sr, e, g);
+            else st<4, false>(dst + e, g);
+        }
+        if (whole && lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+    } else {
+        if (!head || !goes_on) return;
+        int32_t m = 0;                                               // pieces after the first: at bnd, bnd + SEG, ...
+        for (int32_t b0 = bnd; b0 < a.k; b0 += WAVE * SEG) {
+            const int64_t b = (int64_t)b0 + (int64_t)lane * SEG;
+            const bool same = b < a.k && key_row(kw[b]) == r;
+            const unsigned long long mask = __ballot(same);
+            if (mask != ~0ull) { m += __builtin_ctzll(~mask); break; }
+            m += WAVE;
+        }
+        const float *first = a.partials + (2 * bucket + 1) * a.row_len;
+        const float *rest = a.partials + 2 * (bucket + 1) * a.row_len;       // even rows of the following buckets
+        for (int32_t e = lane * 4; e < a.row_len; e += WAVE * 4) {
+            Pack<4> g = ld<4, false>(first + e);
+            for (int32_t q = 0; q < m; q += GATHER) {
+                Pack<4> v[GATHER];
+#pragma unroll
+                for (int u = 0; u < GATHER; ++u)
+                    if (q + u < m) v[u] = ld<4, false>(rest + (int64_t)(q + u) * 2 * a.row_len + e);
+#pragma unroll
+                for (int u = 0; u < GATHER; ++u)
+                    if (q + u < m) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) g.v[c] += v[u].v[c];
+                    }
+            }
+            sparse_row_update(a, xr, br, sr, e, g);
+        }
+        if (lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+    }
+}
+
 // Dirty bitmap -> ascending list of rows.  Three passes: per-block bit counts, scan of the block
 // counts by one block, then each block writes its rows at its offset.
 static constexpr int WORDS_PER_THREAD = 4;
@@ -901,6 +1055,33 @@ hipError_t launch_sparse_step(const SparseArgs &a, hipStream_t s)
     const int64_t nb = (pairs + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (nb > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(sparse_step_kernel, dim3((unsigned)nb), dim3(BLOCK), 0, s, a);
+    return hipGetLastError();
+}
+
+int32_t coalesce_max_k() { return SORT_MAX_K; }
+int64_t coalesce_partial_rows(int32_t W, int32_t k) { return 2 * (int64_t)W * ((k + SEG - 1) / SEG); }
+
+hipError_t launch_sort_rows(const int32_t *idx, uint64_t *keys, int32_t W, int32_t k, int64_t n_rows, hipStream_t s)
+{
+    if (W <= 0 || k < 0 || k > SORT_MAX_K || n_rows <= 0 || n_rows >= (int64_t)ROW_INVALID) return hipErrorInvalidValue;
+    if (k == 0) return hipSuccess;
+    int32_t kp = 2;
+    while (kp < k) kp <<= 1;
+    hipLaunchKernelGGL(sort_rows_kernel, dim3((unsigned)W), dim3(SORT_THREADS), (size_t)kp * sizeof(uint64_t), s, idx, keys,
+                       k, kp, n_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s)
+{
+    const int64_t pairs = (int64_t)a.W * a.k;
+    if (pairs == 0) return hipSuccess;
+    if (!a.keys || !a.partials || a.row_len <= 0 || a.row_len % 4 != 0 || a.n_rows * a.row_len != a.d || a.pitch < a.d || a.pitch % 4 != 0)
+        return hipErrorInvalidValue;
+    const int64_t nb = (pairs + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sparse_step_coalesce_kernel<0>, dim3((unsigned)nb), dim3(BLOCK), 0, s, a);
+    hipLaunchKernelGGL(sparse_step_coalesce_kernel<1>, dim3((unsigned)nb), dim3(BLOCK), 0, s, a);
     return hipGetLastError();
 }
 

@@ -231,6 +231,20 @@ def pin_sparse_equals_dense(lib):
             s.sync(); e.sync(); touched = set()
             assert s.dirty_rows().size == 0
         assert np.array_equal(s.x, e.x) and np.array_equal(s.acc, e.acc) and np.array_equal(s.snap, e.snap)
+    # a row listed several times by one worker: the gradient of that row is the sum of the entries (a batch with a
+    # repeated word), so the step equals the dense step with the summed gradient: acc grows by (sum)^2, not by
+    # the sum of squares, and the denominator is the same for the whole sum
+    s = Oracle(d, W, H, 0.5, 1.0, lib=lib); s.init_state()
+    e = Oracle(d, W, H, 0.5, 1.0, lib=lib); e.init_state()
+    idx = np.array([[2, 9, 2, 2, 5], [0, 0, 1, 1, 11], [7, 3, 4, 6, 7]], dtype=np.int32)
+    vals = rng.integers(-4, 5, size=(W, k, row_len)).astype(np.float64)     # small integers: sums are exact
+    G = np.zeros((W, rows, row_len))
+    for w in range(W):
+        np.add.at(G[w], idx[w], vals[w])
+    s.local_step_sparse(idx, vals, row_len)
+    e.local_step_dense(G.reshape(W, d))
+    assert np.array_equal(s.x, e.x) and np.array_equal(s.acc, e.acc), "repeated rows must add up before the step"
+    assert np.array_equal(s.acc.reshape(W, rows, row_len)[0, 2], 1.0 + (vals[0, 0] + vals[0, 2] + vals[0, 3]) ** 2)
     # untouched rows are exact no-ops
     o = Oracle(d, W, 4, 0.5, 1.0, lib=lib)
     x0 = rng.standard_normal(d); o.init_state(x0)

@@ -587,6 +587,104 @@ def test_sparse_edge_cases(B):
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="mixed period", scale=sc)
 
 
+def _zipf_with_repeats(rows, W, k, rng, s=1.1):
+    """[W][k] rows drawn independently from Zipf(s): popular rows repeat within a worker's list."""
+    z = wl.ZipfRows(rows, s)
+    return np.minimum(np.searchsorted(z.cdf, rng.random((W, k))), rows - 1).astype(np.int32)
+
+
+def _abs_gradient(idx, vals, d, row_len):
+    """sum of |entries| per (worker, coordinate): the magnitude of the terms that make up the summed gradient."""
+    W, k = idx.shape
+    gabs = np.zeros((W, d // row_len, row_len))
+    for w in range(W):
+        np.add.at(gabs[w], idx[w], np.abs(vals[w].astype(np.float64)))
+    return gabs.reshape(W, d)
+
+
+def test_sparse_coalesce_is_bit_identical_on_lists_without_repeats(B):
+    import torch
+    W, rows, row_len, k, H = 4, 3000, 64, 500, 3
+    d = rows * row_len
+    zipf = wl.ZipfRows(rows, 1.1)
+    p = B.LocalAdaAlter(d, W, H, 0.5, 1.0); p.init_state()
+    c = B.LocalAdaAlter(d, W, H, 0.5, 1.0); c.init_state(); c.set_sparse_coalesce(True)
+    for t in range(1, 2 * H + 2):
+        idx, vals = wl.sparse_step(zipf, W, k, row_len, 5, t)
+        di, dv = dev(idx), dev(vals)
+        p.step_sparse(di, dv, row_len); c.step_sparse(di, dv, row_len)
+        assert np.array_equal(p.dirty_rows(), c.dirty_rows())
+    torch.cuda.synchronize()
+    assert torch.equal(p.x, c.x) and torch.equal(p.acc, c.acc) and torch.equal(p.snap, c.snap)
+
+
+@pytest.mark.parametrize("W,rows,row_len,k,H,hot", [(3, 50, 32, 100, 3, False), (8, 5000, 512, 300, 4, False),
+                                                   (2, 7, 4, 1, 2, False), (4, 100, 260, 777, 2, False),
+                                                   (2, 64, 8, 1500, 2, True), (2, 20000, 4, 8192, 2, False)])
+def test_sparse_coalesce_repeated_rows_match_oracle(B, W, rows, row_len, k, H, hot):
+    """Rows that a worker lists several times: the oracle applies Algorithm 3 to the summed gradient; so must the GPU.
+    Bars: the fp32 sum of L entries in list order is off by at most (L-1) 2^-24 of the sum of their magnitudes."""
+    say(f"coalesce W={W} rows={rows} row_len={row_len} k={k} hot={hot}")
+    d = rows * row_len
+    rng = np.random.default_rng(71)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state(x0)
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(dev(x0)); g.set_sparse_coalesce(True)
+    sx = np.abs(o.x); sb = np.ones((W, d))
+    L_max = 1
+    for t in range(1, 2 * H + 2):
+        idx = _zipf_with_repeats(rows, W, k, rng)
+        if hot:
+            idx[0, :] = 5                      # one worker names a single row k times
+        vals = (0.1 * rng.standard_normal((W, k, row_len))).astype(np.float32)
+        L_max = max(L_max, max(np.bincount(idx[w]).max() for w in range(W)))
+        gabs = _abs_gradient(idx, vals, d, row_len)
+        o.local_step_sparse(idx, vals, row_len)
+        g.local_step_sparse(dev(idx), dev(vals), row_len)
+        assert np.array_equal(g.dirty_rows(), o.dirty_rows()), f"dirty rows differ at t={t}"
+        if t % H == 0:
+            o.sync(); g.sync()
+        np.maximum(sx, np.abs(o.x), out=sx); np.maximum(sx, 0.5 * gabs, out=sx)        # eta = 0.5, denominators >= 1
+        np.maximum(sb, gabs * gabs, out=sb)
+        bar = 1e-5 + 2 * (L_max - 1) * 2.0 ** -24
+        ex = np.max(np.abs(host(g.x) - o.x) / np.maximum(sx, 1e-3))
+        eb = np.max(np.abs(host(g.acc) - o.acc) / np.maximum(np.abs(o.acc), sb))
+        es = np.max(np.abs(host(g.snap) - o.snap) / np.maximum(np.abs(o.snap), sb.max(axis=0)))
+        assert ex <= bar and eb <= bar and es <= bar, f"t={t} L_max={L_max}: x {ex:.2e} acc {eb:.2e} snap {es:.2e} > {bar:.1e}"
+    assert L_max > 1 or k == 1
+
+
+def test_sparse_coalesce_bad_rows_and_limit(B):
+    W, rows, row_len, k, H = 2, 40, 8, 12, 2
+    d = rows * row_len
+    rng = np.random.default_rng(73)
+    idx = _zipf_with_repeats(rows, W, k, rng)
+    vals = rng.standard_normal((W, k, row_len)).astype(np.float32)
+    bad = idx.copy(); bad[0, 3] = rows; bad[1, 0] = -7; bad[1, 11] = 2 ** 31 - 1
+    # the oracle sees the same lists with each bad entry replaced by a repeat of another listed row with zero values
+    ok = idx.copy(); ok[0, 3] = idx[0, 0]; ok[1, 0] = idx[1, 1]; ok[1, 11] = idx[1, 1]
+    v_ok = vals.copy(); v_ok[0, 3] = 0; v_ok[1, 0] = 0; v_ok[1, 11] = 0
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state(); g.set_sparse_coalesce(True)
+    g.local_step_sparse(dev(bad), dev(vals), row_len)
+    o.local_step_sparse(ok, v_ok, row_len)
+    assert g.counters(with_bad=True) == (1, 1, 3)
+    assert np.array_equal(g.dirty_rows(), o.dirty_rows())
+    g.sync(); o.sync()
+    gabs = _abs_gradient(ok, v_ok, d, row_len)
+    ex = np.max(np.abs(host(g.x) - o.x) / np.maximum(np.maximum(np.abs(o.x), 0.5 * gabs.max(axis=0)), 1e-3))
+    eb = np.max(np.abs(host(g.acc) - o.acc) / np.maximum(np.abs(o.acc), (gabs * gabs).max(axis=0)))
+    assert ex <= 1e-5 and eb <= 1e-5, f"coalesce with bad rows: x {ex:.2e} acc {eb:.2e}"
+    big = B.LocalAdaAlter(4 * 9000, 1, 2, 0.5, 1.0); big.init_state(); big.set_sparse_coalesce(True)
+    import torch
+    with pytest.raises(B.LaaError):
+        big.local_step_sparse(torch.zeros((1, 8193), dtype=torch.int32, device="cuda:0"),
+                              torch.zeros((1, 8193, 4), device="cuda:0"), 4)
+    big.set_sparse_coalesce(False)             # the plain step has no such limit
+    big.local_step_sparse(torch.arange(8193, dtype=torch.int32, device="cuda:0").reshape(1, -1),
+                          torch.zeros((1, 8193, 4), device="cuda:0"), 4)
+
+
 def test_warmup_learning_rate(B):
     W, H, d, T = 4, 4, 4 * 300, 12
     rng = np.random.default_rng(12)

@@ -7,7 +7,7 @@ import pins
 
 PLANTS = ["ORA_PLANT_RUNNING_DENOM", "ORA_PLANT_NO_SQRT", "ORA_PLANT_PAD_ONE", "ORA_PLANT_PAD_OFF_BY_ONE",
           "ORA_PLANT_PLUS", "ORA_PLANT_ACC_ABS", "ORA_PLANT_SYNC_NO_ACC", "ORA_PLANT_GRAD_OFFSET_SIGN",
-          "ORA_PLANT_SINCOS_SWAPPED", "ORA_PLANT_ADAGRAD_OLD_B2"]
+          "ORA_PLANT_SINCOS_SWAPPED", "ORA_PLANT_ADAGRAD_OLD_B2", "ORA_PLANT_SPARSE_LAST_WINS"]
 
 
 @pytest.mark.parametrize("pin", pins.ALL_PINS, ids=lambda f: f.__name__)
