@@ -117,16 +117,25 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     const int64_t nw = n_dirty_words(n_rows);
     const int64_t nblk = (nw + 1023) / 1024;
     hipError_t e;
-    if ((e = hipMalloc(&h->dirty, nw * sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty bitmap");
-    if ((e = hipMalloc(&h->dirty_list, n_rows * sizeof(int32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty list");
-    if ((e = hipMalloc(&h->dirty_count, sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc dirty count");
-    if ((e = hipMalloc(&h->scan_scratch, (nblk + 1) * sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc scan scratch");
-    if ((e = hipMalloc(&h->bad, sizeof(unsigned long long))) != hipSuccess) return hip_fail(e, "hipMalloc bad-index counter");
+    const char *what = "hipMalloc dirty bitmap";
+    if ((e = hipMalloc(&h->dirty, nw * sizeof(uint32_t))) == hipSuccess) {
+        what = "hipMalloc dirty list";
+        e = hipMalloc(&h->dirty_list, n_rows * sizeof(int32_t));
+    }
+    if (e == hipSuccess) { what = "hipMalloc dirty count"; e = hipMalloc(&h->dirty_count, sizeof(uint32_t)); }
+    if (e == hipSuccess) { what = "hipMalloc scan scratch"; e = hipMalloc(&h->scan_scratch, (nblk + 1) * sizeof(uint32_t)); }
+    if (e == hipSuccess) { what = "hipMalloc bad-index counter"; e = hipMalloc(&h->bad, sizeof(unsigned long long)); }
+    if (e == hipSuccess) { what = "clear dirty bitmap"; e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream); }
+    if (e == hipSuccess) {
+        what = "clear bad-index counter";
+        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 2, h->stream);
+    }
+    if (e != hipSuccess) {
+        free_sparse(h);                   // all or nothing: the next call starts from scratch
+        return hip_fail(e, what);
+    }
     h->n_rows = n_rows;
     h->row_len = row_len;
-    if ((e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream)) != hipSuccess) return hip_fail(e, "clear dirty bitmap");
-    if ((e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 2, h->stream)) != hipSuccess)
-        return hip_fail(e, "clear bad-index counter");
     return LAA_OK;
 }
 
@@ -337,6 +346,7 @@ int laa_init_state(laa_handle h, const float *x0)
 {
     int rc = check_ready(h);
     if (rc != LAA_OK) return rc;
+    if (x0 && !aligned(x0, 4)) return fail(LAA_EALIGN, "x0 not 4-byte aligned");
     const float b0sq = (float)(h->b0 * h->b0);
     hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "init kernel launch");

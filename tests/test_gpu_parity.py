@@ -352,6 +352,31 @@ def test_checkpoint_resume_continues_bit_identically(B):
     assert torch.equal(res.x, ref.x) and torch.equal(res.acc, ref.acc) and torch.equal(res.snap, ref.snap)
 
 
+def test_runs_on_the_callers_stream(B):
+    """All work is enqueued on the stream handed to laa_attach: a side stream here.  Inputs are produced on that stream
+    right before each step (no host synchronisation in between) and results are read after synchronising it alone."""
+    import torch
+    W, H, d = 4, 3, 4 * 64 * 9
+    rng = np.random.default_rng(67)
+    Gs = [rng.standard_normal((W, d)).astype(np.float32) for _ in range(2 * H + 1)]
+    o = Oracle(d, W, H, 0.5, 1.0); o.init_state()
+    sc = parity.Scale(o)
+    side = torch.cuda.Stream(device="cuda:0")
+    with torch.cuda.stream(side):
+        g = B.LocalAdaAlter(d, W, H, 0.5, 1.0)
+        assert g.stream.cuda_stream == side.cuda_stream and side.cuda_stream != 0
+        g.set_lazy_replicas(True); g.init_state()
+        staged = [torch.from_numpy(G).pin_memory() for G in Gs]
+        buf = torch.empty((W, d), device="cuda:0")
+        for G, Gh in zip(Gs, staged):
+            buf.copy_(Gh, non_blocking=True)        # same stream: ordered before the step that reads it
+            g.step_dense(buf)
+            o.step_dense(G); sc.update(o)
+        g.materialize()
+    side.synchronize()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="side stream", scale=sc)
+
+
 def test_sync_due_early_sync_and_noop_sync(B):
     W, H, d = 2, 2, 64
     g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
