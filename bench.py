@@ -47,6 +47,10 @@ def parse():
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--graph", action="store_true",
+                   help="quadratic workloads: run whole periods through laa_run_periods_gen (one HIP graph per period, "
+                        "replayed) on a side stream; for sizes where the launches dominate")
+    p.add_argument("--side-stream", action="store_true", help="run on a non-default stream (as --graph does)")
     p.add_argument("--sparse-repeats", action="store_true",
                    help="workload c4: draw each worker's rows independently (with repeats) and use the coalescing sparse step")
     p.add_argument("--calibrate-copy", type=int, default=0,
@@ -134,6 +138,13 @@ def main():
     B.lib()
     dev = torch.device("cuda:0")
     c = wl.WORKLOADS[args.workload]
+    if args.side_stream and not args.graph:
+        torch.cuda.set_stream(torch.cuda.Stream(device=dev))
+    if args.graph:
+        if c.kind != "quadratic" or args.unfused_sync:
+            print("bench.py: --graph replays whole periods of the fused generator step (workloads c1, c2, c5)", file=sys.stderr)
+            sys.exit(2)
+        torch.cuda.set_stream(torch.cuda.Stream(device=dev))     # the default stream cannot be captured
     H = args.H or c.H
     K, Wm = args.steps, args.warmup
     d, W = c.d, c.W
@@ -257,17 +268,38 @@ def main():
     if c.kind == "embedding":
         mid.update({t + i + 1: torch.cuda.Event(enable_timing=True) for i in range(K)})
     t_first = t + 1
+    if args.graph:
+        K -= K % H
+        g.run_periods_gen(3)                 # the first period of each kind runs as plain launches, the third records
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
-    for i in range(K):
-        t += 1
-        do_step(t)
-        ev[i + 1].record()
+    if args.graph:
+        g.run_periods_gen(K // H)
+        ev[K].record()
+    else:
+        for i in range(K):
+            t += 1
+            do_step(t)
+            ev[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
+    if args.graph:                           # no events inside a replayed period: the average over all iterations
+        assert g.replay_count() >= K // H, "the periods were not replayed from a graph"
+        per_step_ms = [ev[0].elapsed_time(ev[K]) / K] * K
+        graph_inputs = step_bytes // d - (16 * W + 4)
+        lazy_on = not args.no_lazy_replicas
+        if H == 1:
+            period_cols = (8 + graph_inputs + 8) if lazy_on else (16 * W + 8 + graph_inputs)
+        elif lazy_on:    # H - 2 plain steps, the averaging one (writes the collapsed state), the one reading it
+            period_cols = ((H - 2) * (16 * W + 4 + graph_inputs) + (8 * W + 4 + graph_inputs + 8)
+                           + (8 + graph_inputs + 8 * W))
+        else:
+            period_cols = (H - 1) * (16 * W + 4 + graph_inputs) + (16 * W + 8 + graph_inputs)
+        graph_step_bytes = period_cols * d // H
+    else:
+        per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
     if c.kind == "embedding":                 # the roofline line is the row-sparse step alone
         per_step_ms = [ev[i].elapsed_time(mid[t_first + i]) for i in range(K)]
     # the dominant kernel is the plain step: not the averaging one ((i+1) % H == 0) and, with lazy replicas, not the
@@ -285,6 +317,10 @@ def main():
         kernel_name += " (averaging step)"
         plain = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
     plain = plain or per_step_ms
+    if args.graph:
+        plain, step_bytes = per_step_ms, graph_step_bytes
+        kernel_tag += "_graph"
+        kernel_name += " (average over the iterations of a replayed period)"
     post_sync = [per_step_ms[i] for i in range(K) if lazy and i % H == 0 and (i + 1) % H != 0]
     sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
     kern_ms = sum(plain) / len(plain)
@@ -305,7 +341,8 @@ def main():
         "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
-                               f"lazy_replicas={'on' if lazy else 'off'} layout={'+'.join(layouts)}",
+                               f"lazy_replicas={'on' if lazy else 'off'} layout={'+'.join(layouts)}"
+                               f"{' periods replayed from a HIP graph' if args.graph else ''}",
                    "syncs_in_timed_region": len(sync_it),
                    "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
                    "ms_post_sync_iteration": (sum(post_sync) / len(post_sync)) if post_sync else None,

@@ -151,6 +151,20 @@ int laa_set_shard(laa_handle h, int64_t first_column, int32_t first_worker);
 /* One local step with the gradient generated in the kernel at iteration t+1. */
 int laa_local_step_gen(laa_handle h);
 
+/* n_periods whole periods of Algorithm 3 with the generator: each is H calls of laa_step_gen (the
+ * last one averages).  Must be called right after a sync (or at the start).  The H kernel launches
+ * of a period are recorded once into a HIP graph and replayed, which removes most of the launch cost
+ * when d is small enough for the launches to dominate; the iteration number the generator needs is
+ * read from a device word that the graph advances.  Results are bit-identical to the same number of
+ * laa_step_gen calls.  Periods run as plain launches instead (same results) on the legacy default
+ * stream (null), which cannot be captured, during the warm-up of the learning rate, when the arrays
+ * are not 16-byte aligned or d is not a multiple of 4, with laa_set_tile(h, 0), and the first time
+ * after the configuration changed.  Allocates 8 bytes of device memory on first use. */
+int laa_run_periods_gen(laa_handle h, int32_t n_periods);
+
+/* How many periods laa_run_periods_gen has run by graph replay (the others ran as plain launches). */
+int laa_get_replay_count(laa_handle h, int64_t *periods_replayed);
+
 /* Write the gradient the next generator step would use into out [W][d] (device),
  * without stepping.  For tests and for pre-computing gradient pools. */
 int laa_generate_gradient(laa_handle h, float *out);

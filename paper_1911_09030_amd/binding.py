@@ -22,7 +22,7 @@ ALGO_LOCAL_ADAALTER, ALGO_DIST_ADAGRAD, ALGO_LOCAL_SGD = 0, 1, 2
 EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
     "laa_set_tile", "laa_set_lazy_replicas", "laa_set_sparse_coalesce", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
-    "laa_local_step_gen", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
+    "laa_local_step_gen", "laa_run_periods_gen", "laa_get_replay_count", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_set_shard", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
     "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
 ]
@@ -71,6 +71,8 @@ def lib():
         "laa_step_sparse": [vp, vp, vp, i32, i32],
         "laa_get_counters": [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)],
         "laa_set_counters": [vp, i64, i32],
+        "laa_run_periods_gen": [vp, i32],
+        "laa_get_replay_count": [vp, C.POINTER(i64)],
         "laa_set_sparse_coalesce": [vp, i32],
         "laa_set_shard": [vp, i64, i32],
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
@@ -300,6 +302,14 @@ class LocalAdaAlter:
 
     def set_sparse_coalesce(self, on=True):
         _check(self.L.laa_set_sparse_coalesce(self.h, 1 if on else 0))
+
+    def run_periods_gen(self, n_periods=1):
+        _check(self.L.laa_run_periods_gen(self.h, int(n_periods)))
+
+    def replay_count(self):
+        n = C.c_int64(0)
+        _check(self.L.laa_get_replay_count(self.h, C.byref(n)))
+        return n.value
 
     def set_shard(self, first_column=0, first_worker=0):
         _check(self.L.laa_set_shard(self.h, int(first_column), int(first_worker)))

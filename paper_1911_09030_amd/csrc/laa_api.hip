@@ -50,6 +50,20 @@ struct laa_ctx {
     double *diag_scratch = nullptr;   // block partials + results of laa_diagnostics
     bool sparse_only_since_sync = true;   // every step since the last sync was a sparse one
     uint64_t bytes = 0;
+    // replayed periods (laa_run_periods_gen): one captured graph per state the period can start in
+    struct PeriodGraph {
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        uint64_t epoch = 0;               // configuration the graph was captured for
+        bool warmed = false;              // an eager period of this kind has run (kernels loaded) at that epoch
+        uint64_t warmed_epoch = 0;
+        bool end_collapsed = false;
+        uint64_t bytes = 0;               // algorithmic bytes of one period
+    } period[2];                          // [0]: starts from full replicas, [1]: from the collapsed state
+    uint64_t epoch = 1;                   // bumped whenever something a captured kernel argument depends on changes
+    uint32_t *t_dev = nullptr;            // device word: iteration count at the start of the period being replayed
+    bool capturing = false;
+    int64_t replays = 0;                  // periods run by graph replay so far
 };
 
 namespace {
@@ -89,6 +103,18 @@ int check_ready(laa_handle h)
     return LAA_OK;
 }
 
+void drop_period_graphs(laa_ctx *h)
+{
+    for (auto &p : h->period) {
+        if (p.exec) (void)hipGraphExecDestroy(p.exec);
+        if (p.graph) (void)hipGraphDestroy(p.graph);
+        p = laa_ctx::PeriodGraph();
+    }
+}
+
+// Something a captured kernel argument depends on has changed: captured periods are stale.
+void config_changed(laa_ctx *h) { h->epoch += 1; }
+
 void free_sparse(laa_ctx *h)
 {
     if (h->dirty) (void)hipFree(h->dirty);
@@ -102,6 +128,7 @@ void free_sparse(laa_ctx *h)
     h->partials = nullptr; h->partial_cap = 0;
     h->dirty = nullptr; h->dirty_list = nullptr; h->dirty_count = nullptr; h->scan_scratch = nullptr; h->bad = nullptr;
     h->n_rows = 0; h->row_len = 0;
+    config_changed(h);                    // the fused sync's bitmap clear is part of a captured period
 }
 
 int64_t n_dirty_words(int64_t n_rows) { return (n_rows + 31) / 32; }
@@ -136,6 +163,7 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     }
     h->n_rows = n_rows;
     h->row_len = row_len;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -190,6 +218,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.col0 = h->col0; a.w0 = h->w0;
     a.t_lo = (uint32_t)(h->t + 1);
+    a.t_dev = h->capturing ? h->t_dev : nullptr;
     a.grad_source = kind == STEP_DENSE ? laa::GRAD_EXPLICIT : h->gen_mode;
     a.off_source = kind == STEP_DENSE ? laa::OFFSET_NONE : h->off_mode;
     a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
@@ -249,6 +278,8 @@ int laa_destroy(laa_handle h)
 {
     if (!h) return LAA_OK;
     free_sparse(h);
+    drop_period_graphs(h);
+    if (h->t_dev) (void)hipFree(h->t_dev);
     if (h->diag_scratch) (void)hipFree(h->diag_scratch);
     delete h;
     return LAA_OK;
@@ -260,6 +291,7 @@ int laa_set_b0(laa_handle h, double b0)
     if (!(b0 >= 0.0) || !std::isfinite(b0)) return fail(LAA_EINVAL, "b0 must be finite and >= 0");
     if (h->t != 0) return fail(LAA_EINVAL, "b0 can only be set before the first step");
     h->b0 = b0;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -268,6 +300,7 @@ int laa_set_warmup(laa_handle h, int64_t warmup_steps)
     if (!h) return fail(LAA_EINVAL, "null handle");
     if (warmup_steps < 0) return fail(LAA_EINVAL, "warmup_steps must be >= 0");
     h->warmup_steps = warmup_steps;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -277,6 +310,7 @@ int laa_set_algorithm(laa_handle h, int32_t algo)
     if (algo < LAA_ALGO_LOCAL_ADAALTER || algo > LAA_ALGO_LOCAL_SGD) return fail(LAA_EINVAL, "unknown update rule %d", algo);
     if (h->t != 0) return fail(LAA_EINVAL, "the update rule can only be chosen before the first step");
     h->algo = algo;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -287,12 +321,14 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch)
     if (wt == 0) {              // one worker per thread block in non-sync steps
         h->split = true;
         h->wt = pick_wt(h->W);
+        config_changed(h);
         return LAA_OK;
     }
     if (!(wt == 1 || wt == 2 || wt == 4 || wt == 8) || h->W % wt != 0)
         return fail(LAA_EINVAL, "workers_per_batch must be 0, or 1, 2, 4 or 8 and divide W");
     h->wt = wt;
     h->split = false;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -305,6 +341,7 @@ int laa_set_lazy_replicas(laa_handle h, int32_t on)
         if (rc != LAA_OK) return rc;
     }
     h->lazy = on != 0;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -339,6 +376,7 @@ int laa_attach_pitched(laa_handle h, float *x, float *acc, float *snap, int64_t 
     h->pitch = pitch;
     h->vec4 = h->d % 4 == 0 && pitch % 4 == 0 && aligned(x, 16) && aligned(acc, 16) && aligned(snap, 16);
     h->attached = true;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -371,6 +409,7 @@ int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a,
     h->gen_mode = mode; h->off_mode = off_mode; h->seed = seed;
     h->a = a; h->xstar = xstar; h->off = off;
     h->noise_scale = noise_scale; h->off_scale = off_scale;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -382,6 +421,7 @@ int laa_set_shard(laa_handle h, int64_t first_column, int32_t first_worker)
     if (first_column > INT64_MAX - h->d) return fail(LAA_EINVAL, "first_column + d overflows");
     if (first_worker < 0 || first_worker > INT32_MAX - h->W) return fail(LAA_EINVAL, "bad first_worker %d", first_worker);
     h->col0 = first_column; h->w0 = first_worker;
+    config_changed(h);
     return LAA_OK;
 }
 
@@ -389,6 +429,96 @@ int laa_local_step_dense(laa_handle h, const float *grads) { return dense_step(h
 int laa_local_step_gen(laa_handle h) { return dense_step(h, STEP_GEN, nullptr, false); }
 int laa_step_dense(laa_handle h, const float *grads) { return dense_step(h, STEP_DENSE, grads, true); }
 int laa_step_gen(laa_handle h) { return dense_step(h, STEP_GEN, nullptr, true); }
+
+// One period = H generator steps, the last one with the averaging fused in.
+static int eager_period(laa_handle h)
+{
+    for (int32_t k = 0; k < h->H; ++k) {
+        const int rc = dense_step(h, STEP_GEN, nullptr, true);
+        if (rc != LAA_OK) return rc;
+    }
+    return LAA_OK;
+}
+
+int laa_run_periods_gen(laa_handle h, int32_t n_periods)
+{
+    int rc = check_ready(h);
+    if (rc != LAA_OK) return rc;
+    if (n_periods < 0) return fail(LAA_EINVAL, "n_periods must be >= 0");
+    if (h->gen_mode == 0) return fail(LAA_EMODE, "no gradient generator configured (laa_set_generator)");
+    if (h->algo != LAA_ALGO_LOCAL_ADAALTER) return fail(LAA_EMODE, "replayed periods exist for Local AdaAlter only");
+    if (h->s != 0) return fail(LAA_EINVAL, "%d local steps since the last sync: a period must start right after one", h->s);
+    hipError_t e;
+    for (int32_t n = 0; n < n_periods; ++n) {
+        const int c = h->collapsed ? 1 : 0;
+        laa_ctx::PeriodGraph &pg = h->period[c];
+        // The learning rate is an argument of the captured kernels: periods inside the warm-up run eagerly.  So does
+        // everything on the legacy default stream, which cannot be captured, and the first period of each kind,
+        // so that no kernel is launched for the first time under capture.
+        const bool in_warmup = h->warmup_steps > 0 && h->t < h->warmup_steps;
+        const bool warmed = pg.warmed && pg.warmed_epoch == h->epoch;
+        const bool vector_path = h->vec4 && h->gen_aligned16 && !h->split;   // the kernels with a device iteration word
+        if (in_warmup || h->stream == nullptr || !warmed || !vector_path) {
+            if ((rc = eager_period(h)) != LAA_OK) return rc;
+            if (!in_warmup) { pg.warmed = true; pg.warmed_epoch = h->epoch; }
+            continue;
+        }
+        if (!h->t_dev) {
+            if ((e = hipMalloc(&h->t_dev, 2 * sizeof(uint32_t))) != hipSuccess) return hip_fail(e, "hipMalloc iteration word");
+        }
+        if (!pg.exec || pg.epoch != h->epoch) {
+            if (pg.exec) (void)hipGraphExecDestroy(pg.exec);
+            if (pg.graph) (void)hipGraphDestroy(pg.graph);
+            pg.exec = nullptr; pg.graph = nullptr;
+            // Record the H launches of one period with iteration numbers 1..H relative to the device word, which the
+            // last node of the graph advances by H.  Nothing runs during capture; the host state is put back after.
+            const int64_t t_saved = h->t, warm_saved = h->warmup_steps;
+            const uint64_t bytes_saved = h->bytes;
+            if ((e = hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
+                return hip_fail(e, "hipStreamBeginCapture");
+            h->capturing = true; h->t = 0; h->warmup_steps = 0;
+            rc = eager_period(h);
+            hipError_t e_bump = rc == LAA_OK ? laa::launch_add_u32(h->t_dev, (uint32_t)h->H, h->stream) : hipSuccess;
+            h->capturing = false; h->t = t_saved; h->warmup_steps = warm_saved;
+            pg.end_collapsed = h->collapsed;
+            pg.bytes = h->bytes - bytes_saved;
+            h->bytes = bytes_saved;
+            h->collapsed = c != 0;
+            e = hipStreamEndCapture(h->stream, &pg.graph);            // always leave capture mode
+            if (rc != LAA_OK) { if (pg.graph) (void)hipGraphDestroy(pg.graph); pg.graph = nullptr; return rc; }
+            if (e_bump != hipSuccess) e = e_bump;
+            if (e == hipSuccess) e = hipGraphInstantiate(&pg.exec, pg.graph, nullptr, nullptr, 0);
+            if (e != hipSuccess) {
+                if (pg.graph) (void)hipGraphDestroy(pg.graph);
+                pg.graph = nullptr; pg.exec = nullptr;
+                return hip_fail(e, "capturing a period into a HIP graph");
+            }
+            pg.epoch = h->epoch;
+        }
+        // consecutive periods of the same kind: set the device word once, replay back to back
+        if ((e = laa::launch_fill_u32(h->t_dev, (uint32_t)h->t, 1, h->stream)) != hipSuccess)
+            return hip_fail(e, "setting the iteration word");
+        while (true) {
+            if ((e = hipGraphLaunch(pg.exec, h->stream)) != hipSuccess) return hip_fail(e, "hipGraphLaunch");
+            h->t += h->H;
+            h->replays += 1;
+            h->bytes += pg.bytes;
+            h->collapsed = pg.end_collapsed;
+            h->sparse_only_since_sync = true;
+            const bool next_in_warmup = h->warmup_steps > 0 && h->t < h->warmup_steps;
+            if (n + 1 < n_periods && (h->collapsed ? 1 : 0) == c && !next_in_warmup) ++n;
+            else break;
+        }
+    }
+    return LAA_OK;
+}
+
+int laa_get_replay_count(laa_handle h, int64_t *periods_replayed)
+{
+    if (!h || !periods_replayed) return fail(LAA_EINVAL, "null argument");
+    *periods_replayed = h->replays;
+    return LAA_OK;
+}
 
 int laa_generate_gradient(laa_handle h, float *out)
 {

@@ -30,6 +30,7 @@ struct StepArgs {
     int64_t col0;        // global index of column 0 (multiple of 4) and
     int32_t w0;          // global index of worker 0: the generator's counters are global
     uint32_t t_lo;       // iteration number of this step (low 32 bits), Philox counter word
+    const uint32_t *t_dev; // if not null: a device word added to t_lo (iteration count at the start of a replayed graph)
     int32_t grad_source, off_source;
     bool sync;           // average over the worker axis in the same pass
     bool vec4;           // pointers 16-byte aligned and d % 4 == 0
@@ -48,6 +49,8 @@ hipError_t launch_materialize(float *x, float *acc, const float *snap, int64_t d
 hipError_t launch_init(float *x, float *acc, float *snap, const float *x0, float b0sq, int64_t d, int64_t pitch,
                        int32_t W, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
+// *p += v by one thread (the iteration counter of a replayed period)
+hipError_t launch_add_u32(uint32_t *p, uint32_t v, hipStream_t s);
 
 struct SparseArgs {
     float *x, *acc, *snap;

@@ -139,7 +139,8 @@ static constexpr uint32_t STREAM_OFFSET = 2, STREAM_NOISE = 3;
 
 // Gradient of worker w for the VEC coordinates starting at j, evaluated at xv (the worker's x before the step).
 //   quadratic: g = a (x - (xstar + off)) + noise_scale n        noise: g = a n
-template <int VEC, int GS, int OS>
+// TDEV: the iteration number is t_lo plus a device word (periods replayed from a graph).
+template <int VEC, int GS, int OS, bool TDEV = false>
 __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int64_t row, int32_t w,
                                               const Pack<VEC> &xv, const Pack<VEC> &av, const Pack<VEC> &xs)
 {
@@ -150,7 +151,9 @@ __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int6
         const uint64_t qa = (uint64_t)(j + a.col0) >> 2;      // col0 % 4 == 0: j & 3 is the global lane too
         const uint32_t wg = (uint32_t)(w + a.w0);
         float n[4];
-        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, wg, a.t_lo, n);
+        uint32_t t = a.t_lo;
+        if constexpr (TDEV) t += *a.t_dev;                       // uniform: one scalar load
+        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, wg, t, n);
         if constexpr (GS == GRAD_NOISE) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) g.v[e] = av.v[e] * n[VEC == 4 ? e : (int)(j & 3)];
@@ -202,7 +205,7 @@ template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const P
 // state is kept once (x in row 0, B2 in snap):
 //   CIN : the state is collapsed on entry: read x from row 0 and B2 from snap for every worker
 //   COUT: (with SYNC) leave it collapsed: write the means to row 0 of x and to snap only
-template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool CIN, bool COUT>
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool CIN, bool COUT, bool TDEV>
 __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, const int32_t w_begin,
                                           const int32_t w_end)
 {
@@ -236,7 +239,7 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
             const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
-            const Pack<VEC> g = gradient<VEC, GS, OS>(a, j, row, w0 + i, xv[i], av, xs);
+            const Pack<VEC> g = gradient<VEC, GS, OS, TDEV>(a, j, row, w0 + i, xv[i], av, xs);
             if constexpr (GRAD_ONLY) {
                 st<VEC, NT_ST>(a.grad_out + row, g);
             } else {
@@ -274,7 +277,7 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
     }
 }
 
-template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT, bool CIN, bool COUT>
+template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT, bool CIN, bool COUT, bool TDEV = false>
 __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
 {
     static_assert(!SPLIT || (WT == 1 && !SYNC), "a split block owns one worker and cannot average");
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
     int64_t j;
     int32_t w_begin, w_end;
     if (block_work<VEC, SPLIT>(a.d, a.W, &j, &w_begin, &w_end))
-        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT>(a, j, w_begin, w_end);
+        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT, TDEV>(a, j, w_begin, w_end);
 }
 
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
@@ -432,6 +435,11 @@ __global__ __launch_bounds__(BLOCK) void fill_u32_kernel(uint32_t *p, uint32_t v
 {
     const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+__global__ void add_u32_kernel(uint32_t *p, uint32_t v)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p += v;
 }
 
 __global__ __launch_bounds__(BLOCK) void copy_kernel(v4f *__restrict__ dst, const v4f *__restrict__ src, int64_t n4)
@@ -871,6 +879,27 @@ static hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t s)
 {
 #define LAA_STEP(SYNC, GONLY, SPLIT, CIN, COUT) \
     hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, SYNC, GONLY, SPLIT, CIN, COUT>), grid, dim3(DBLOCK), 0, s, a)
+#define LAA_STEP_T(SYNC, CIN, COUT) \
+    hipLaunchKernelGGL((step_kernel<VEC, WT, GS, OS, SYNC, false, false, CIN, COUT, true>), grid, dim3(DBLOCK), 0, s, a)
+    if (a.t_dev) {              // a step of a replayed period: vector path, generator, Local AdaAlter, all workers per block
+        if constexpr (VEC == 4 && GS != GRAD_EXPLICIT) {
+            if (a.grad_out || a.split || a.algo != ALGO_LOCAL_ADAALTER) return hipErrorInvalidValue;
+            if (a.sync) {
+                if (a.collapsed_in && a.collapsed_out) LAA_STEP_T(true, true, true);
+                else if (a.collapsed_in) LAA_STEP_T(true, true, false);
+                else if (a.collapsed_out) LAA_STEP_T(true, false, true);
+                else LAA_STEP_T(true, false, false);
+            } else if (a.collapsed_in) {
+                LAA_STEP_T(false, true, false);
+            } else {
+                LAA_STEP_T(false, false, false);
+            }
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+#undef LAA_STEP_T
     if (a.grad_out) {
         if constexpr (GS == GRAD_EXPLICIT) return hipErrorInvalidValue;
         else if (a.collapsed_in) LAA_STEP(false, true, false, true, false);
@@ -997,6 +1026,13 @@ hipError_t launch_materialize(float *x, float *acc, const float *snap, int64_t d
     dim3 grid;
     if (!grid_for(d, &grid) || pitch < d) return hipErrorInvalidValue;
     hipLaunchKernelGGL(materialize_kernel, grid, dim3(BLOCK), 0, s, x, acc, snap, d, pitch, W);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_u32(uint32_t *p, uint32_t v, hipStream_t s)
+{
+    if (!p) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(add_u32_kernel, dim3(1), dim3(WAVE), 0, s, p, v);
     return hipGetLastError();
 }
 

@@ -76,6 +76,7 @@ def test_host_error_paths(L):
     assert L.laa_attach(h, C.c_void_p(2), C.c_void_p(16), C.c_void_p(16), None) == binding.EALIGN
     t, s = C.c_int64(-1), C.c_int32(-1)
     assert L.laa_get_counters(h, C.byref(t), C.byref(s), None) == binding.OK and (t.value, s.value) == (0, 0)
+    assert L.laa_run_periods_gen(h, 1) == binding.ENOTATTACHED
     assert L.laa_set_shard(h, 6, 0) == binding.EINVAL            # not a multiple of 4
     assert L.laa_set_shard(h, -4, 0) == binding.EINVAL
     assert L.laa_set_shard(h, 8, -1) == binding.EINVAL

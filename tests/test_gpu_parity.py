@@ -377,6 +377,51 @@ def test_runs_on_the_callers_stream(B):
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="side stream", scale=sc)
 
 
+@pytest.mark.parametrize("lazy,H,warmup,side,replays", [(True, 4, 0, True, 7), (False, 3, 0, True, 8),
+                                                          (True, 1, 0, True, 7), (True, 2, 5, True, 5),
+                                                          (True, 4, 0, False, 0)])
+def test_replayed_periods_equal_step_by_step(B, lazy, H, warmup, side, replays):
+    """laa_run_periods_gen (one HIP graph per period, replayed) against the same number of laa_step_gen calls: bit for
+    bit after every call, with eager work, synchronisations and reads between the replays."""
+    import torch
+    say(f"graph periods lazy={lazy} H={H} warmup={warmup} side_stream={side}")
+    W, d = 4, 4 * 64 * 5
+    rng = np.random.default_rng(83)
+    stream = torch.cuda.Stream(device="cuda:0") if side else torch.cuda.current_stream()
+    with torch.cuda.stream(stream):
+        a = dev(rng.uniform(0.1, 10, d).astype(np.float32)); xs = dev(rng.standard_normal(d).astype(np.float32))
+        torch.cuda.synchronize()
+        pair = []
+        for _ in range(2):
+            u = B.LocalAdaAlter(d, W, H, 0.5, 1.0); u.set_lazy_replicas(lazy); u.set_warmup(warmup); u.init_state()
+            u.set_generator(B.GEN_QUADRATIC, 21, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+            pair.append(u)
+        ref, g = pair
+        for n in (1, 2, 1, 3, 2):
+            for _ in range(n * H):
+                ref.step_gen()
+            g.run_periods_gen(n)
+            assert g.counters() == ref.counters()
+            dg, dr = g.diagnostics(), ref.diagnostics()          # synchronises; reads the (possibly collapsed) state
+            assert dg == dr
+            g.step_gen(); ref.step_gen()                          # eager work between the replays ...
+            for _ in range(H - 1):
+                g.step_gen(); ref.step_gen()                      # ... up to the next period boundary
+            torch.cuda.synchronize()
+            g.materialize(); ref.materialize()
+            torch.cuda.synchronize()
+            assert torch.equal(g.x, ref.x) and torch.equal(g.acc, ref.acc) and torch.equal(g.snap, ref.snap), n
+            assert g.bytes_moved() == ref.bytes_moved()
+    # 9 periods asked for (each call starts from full replicas because of the materialize above); the first of each
+    # kind (from full replicas, from the collapsed state) outside the warm-up and those inside the
+    # warm-up run as plain launches, and so does everything on the default stream
+    assert g.replay_count() == replays and ref.replay_count() == 0
+    if H > 1:
+        g.local_step_gen()
+        with pytest.raises(B.LaaError):
+            g.run_periods_gen(1)                                  # not at a period boundary
+
+
 def test_sync_due_early_sync_and_noop_sync(B):
     W, H, d = 2, 2, 64
     g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
