@@ -39,7 +39,8 @@ def parse():
     p.add_argument("--hold-gaps", action="store_true",
                    help="spread layout as one ordinary allocation that includes the gaps (instead of laa_spread_alloc)")
     p.add_argument("--unfused-sync", action="store_true", help="local step and laa_sync as two kernels")
-    p.add_argument("--tile", type=int, default=0, help="workers loaded per batch (laa_set_tile)")
+    p.add_argument("--tile", type=int, default=None,
+                   help="laa_set_tile: workers loaded per batch (1, 2, 4, 8), or 0 for one worker per thread block")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
     p.add_argument("--layout", default="spread", choices=["spread", "packed"],
                    help="spread: all [W][d] rows and [d] vectors up to 10 GB apart over the HBM address range "
@@ -246,7 +247,7 @@ def main():
                 mid[t].record()
             gd.step_gen()
         updates_per_step = W * c.k * c.row_len + W * dd
-    if args.tile:
+    if args.tile is not None:
         g.set_tile(args.tile)
     lazy = not args.no_lazy_replicas and c.kind != "embedding"
     if lazy:
