@@ -52,7 +52,7 @@ def test_philox_words_bit_exact(B):
 
 @pytest.mark.parametrize("W,H,d", [(4, 4, D_SMALL), (8, 8, D_SMALL), (1, 3, 4 * 300), (2, 2, 4 * 1000),
                                    (3, 5, 4 * 777), (5, 2, 4 * 513), (16, 4, 4 * 2049), (12, 3, 4 * 700),
-                                   (4, 4, 4 * 256 * 3 + 3), (8, 2, 1023), (2, 4, 1)])
+                                   (4, 4, 4 * 256 * 3 + 3), (8, 2, 1023), (2, 4, 1), (64, 2, 4 * 130), (7, 50, 4 * 64)])
 def test_dense_explicit_one_step_and_full_run(B, W, H, d):
     """Same gradient bits on both sides: <= 1e-6 after one step, <= 1e-5 after T steps with syncs."""
     say(f"dense explicit W={W} H={H} d={d}")
