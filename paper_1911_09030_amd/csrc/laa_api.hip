@@ -616,7 +616,7 @@ int laa_sync(laa_handle h)
     if (h->dirty && h->sparse_only_since_sync && !x_only) {
         e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
-        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->row_len, h->dirty_list, h->dirty_count, h->stream);
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, h->dirty_list, h->dirty_count, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
         const bool collapse = h->lazy && !x_only;

@@ -1133,14 +1133,18 @@ hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *
     return hipGetLastError();
 }
 
-hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t row_len,
+hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,
                             const int32_t *list, const uint32_t *count, hipStream_t s)
 {
+    if (W <= 0 || wt <= 0 || W % wt != 0 || row_len <= 0 || row_len % 4 != 0) return hipErrorInvalidValue;
     const dim3 grid(2048), block(BLOCK);
-    if (W % 8 == 0) hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
-    else if (W % 4 == 0) hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
-    else if (W % 2 == 0) hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
-    else hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count);
+    switch (wt) {               // the same batches as the dense mean: one order of the worker-axis sum everywhere
+    case 8: hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
+    case 4: hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
+    case 2: hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
+    case 1: hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -657,6 +657,29 @@ def test_sparse_edge_cases(B):
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="mixed period", scale=sc)
 
 
+@pytest.mark.parametrize("W,tile", [(8, 8), (8, 4), (8, 2), (4, 1), (2, 2)])
+def test_sparse_sync_equals_dense_sync_bit_for_bit(B, W, tile):
+    """After sparse-only steps the averaging touches the listed rows only.  For W a power of two the mean of equal
+    values is exact, so this must equal the averaging of the whole table bit for bit, with the same batches of workers
+    (laa_set_tile) in both."""
+    import torch
+    rows, row_len, k, H = 300, 16, 40, 3
+    d = rows * row_len
+    zipf = wl.ZipfRows(rows, 1.1)
+    x0 = dev(np.random.default_rng(91).standard_normal(d).astype(np.float32))
+    sp = B.LocalAdaAlter(d, W, H, 0.5, 1.0); sp.set_tile(tile); sp.init_state(x0)
+    de = B.LocalAdaAlter(d, W, H, 0.5, 1.0); de.set_tile(tile); de.init_state(x0)
+    for period in range(2):
+        for t in range(1, H + 1):
+            idx, vals = wl.sparse_step(zipf, W, k, row_len, 17, period * H + t)
+            sp.local_step_sparse(dev(idx), dev(vals), row_len)
+            de.local_step_sparse(dev(idx), dev(vals), row_len)
+        de.set_counters(*de.counters())          # forgets which rows were touched: the next sync averages everything
+        sp.sync(); de.sync()
+        torch.cuda.synchronize()
+        assert torch.equal(sp.x, de.x) and torch.equal(sp.acc, de.acc) and torch.equal(sp.snap, de.snap), period
+
+
 def _zipf_with_repeats(rows, W, k, rng, s=1.1):
     """[W][k] rows drawn independently from Zipf(s): popular rows repeat within a worker's list."""
     z = wl.ZipfRows(rows, s)
