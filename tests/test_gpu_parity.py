@@ -78,6 +78,28 @@ def test_dense_explicit_one_step_and_full_run(B, W, H, d):
     say("   rel err x/acc/snap", e)
 
 
+@pytest.mark.parametrize("eta,eps,b0", [(0.5, 0.0, 1.0), (0.05, 1e-3, 0.5), (2.0, 10.0, 3.0), (-0.1, 1.0, 1.0),
+                                        (1e-3, 1e-2, 1.0)])
+def test_hyperparameters(B, eta, eps, b0):
+    """Step size, epsilon and b0 away from the defaults (eps = 0 leaves sqrt(B2) alone under the root; a negative
+    step size is ascent; b0 < 1 is outside the theorem's assumption but inside the algorithm)."""
+    W, H, d = 4, 3, 4 * 64 * 3 + 8
+    rng = np.random.default_rng(97)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, eta, eps, b0); o.init_state(x0)
+    g = B.LocalAdaAlter(d, W, H, eta, eps, b0=b0); g.set_lazy_replicas(True); g.init_state(dev(x0))
+    sc = parity.Scale(o)
+    for t in range(1, 3 * H + 2):
+        G = rng.standard_normal((W, d)).astype(np.float32)
+        o.step_dense(G); g.step_dense(dev(G)); sc.update(o)
+        if t == 1:
+            parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.ONE_STEP, what="one step", scale=sc,
+                                floor_b=1e-3 * b0 * b0)
+    g.materialize()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what=f"eta={eta} eps={eps} b0={b0}",
+                        scale=sc, floor_b=1e-3 * b0 * b0)
+
+
 def test_unaligned_buffers_take_scalar_path(B):
     import torch
     W, H, d = 4, 2, 4 * 500
