@@ -980,12 +980,13 @@ def test_config4_embedding_table_sampled_rows(B):
     """800,000 x 512 table, W=8, k=8192 Zipf(1.1) rows per worker and step; oracle follows a sample of rows."""
     import torch
     c = wl.WORKLOADS["c4"]
-    H = 4
+    H, T = c.H, 2 * c.H + 1                 # two periods of the configuration's H = 16 and one step more
     zipf = wl.ZipfRows(c.rows, c.zipf_s)
     g = B.LocalAdaAlter(c.d, c.W, H, c.eta, c.eps); g.init_state()
-    steps = [wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, c.val_sigma) for t in range(1, H + 2)]
+    all_idx = [wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, with_vals=False)[0] for t in range(1, T + 1)]
+    steps = (wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, c.val_sigma) for t in range(1, T + 1))
     # sample: the 8 hottest rows, 24 rows drawn from those touched, 8 rows never touched
-    touched = np.unique(np.concatenate([s[0].ravel() for s in steps]))
+    touched = np.unique(np.concatenate([i.ravel() for i in all_idx]))
     rng = np.random.default_rng(4)
     never = np.setdiff1d(np.arange(c.rows), touched)[:8]
     sample = np.unique(np.concatenate([np.arange(8), rng.choice(touched, 24, replace=False), never]))
@@ -994,6 +995,7 @@ def test_config4_embedding_table_sampled_rows(B):
     union = set()
     sc = parity.Scale(o)
     for t, (idx, vals) in enumerate(steps, start=1):
+        assert np.array_equal(idx, all_idx[t - 1])
         g.local_step_sparse(dev(idx), dev(vals), c.row_len)
         # the oracle sees each worker's sampled rows only (padded per worker to a common k with zero rows is not
         # needed: a dense step on the scattered gradient is the definition)
