@@ -800,6 +800,110 @@ def test_sparse_coalesce_bad_rows_and_limit(B):
                           torch.zeros((1, 8193, 4), device="cuda:0"), 4)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_call_sequences_follow_the_oracle(B, seed):
+    """Seeded random sequences over the whole boundary (explicit, generated and row-sparse steps, local and fused;
+    early, due and empty syncs; lazy replicas and row coalescing switched on and off; materialize; resume; whole
+    periods; diagnostics; dirty rows; tile changes)
+    against the same calls on the oracle.  The test keeps its own model of when the state is held collapsed (row 0 of
+    x and snap), so that it reads only what is defined and never disturbs the library's bookkeeping."""
+    import torch
+    rng = np.random.default_rng(1000 + seed)
+    W, H = int(rng.choice([2, 4, 8])), int(rng.integers(1, 5))
+    rows, row_len = 48, 8
+    d = rows * row_len
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.3, 0.5); o.init_state(x0)
+    o.set_generator(oracle.GEN_QUADRATIC, seed, a, xs, None, oracle.OFF_PHILOX, 0.1, 0.1)
+    g = B.LocalAdaAlter(d, W, H, 0.3, 0.5); g.init_state(dev(x0))
+    g.set_generator(B.GEN_QUADRATIC, seed, dev(a), dev(xs), None, B.OFF_PHILOX, 0.1, 0.1)
+    m = {"lazy": False, "collapsed": False, "sparse_only": True, "sparse_ever": False, "coalesce": False,
+         "dirty_known": True}
+    log = []
+
+    def averaged_by_sync():           # laa_sync with steps pending (also the tail of a fused sparse step)
+        if not (m["sparse_only"] and m["sparse_ever"]):
+            m["collapsed"] = m["lazy"]                 # whole-table mean; touched rows only leave it expanded
+        m["sparse_only"] = True
+
+    for n in range(60):
+        s_before = o.steps_since_sync
+        ops = ["sync", "lazy", "materialize", "diag", "dirty", "tile", "coalesce", "resume"]
+        if s_before < H:
+            ops += ["dense", "dense", "gen", "gen", "sparse", "sparse", "ldense", "lgen", "lsparse"]
+        if s_before == 0:
+            ops += ["periods"]
+        op = str(rng.choice(ops))
+        log.append(op)
+        if op in ("dense", "ldense", "gen", "lgen"):
+            if op.endswith("dense"):
+                G = rng.standard_normal((W, d)).astype(np.float32)
+                (g.step_dense if op == "dense" else g.local_step_dense)(dev(G))
+                (o.step_dense if op == "dense" else o.local_step_dense)(G)
+            else:
+                (g.step_gen if op == "gen" else g.local_step_gen)()
+                (o.step_gen if op == "gen" else o.local_step_gen)()
+            m["collapsed"], m["sparse_only"] = False, False
+            if o.steps_since_sync == 0:                # the fused step averaged in the same pass
+                m["collapsed"], m["sparse_only"] = m["lazy"], True
+        elif op in ("sparse", "lsparse"):
+            k = int(rng.integers(0, 20))
+            idx = np.stack([rng.permutation(rows)[:k] for _ in range(W)]).astype(np.int32).reshape(W, k)
+            if m["coalesce"] and k:                    # lists may then name a row several times
+                idx = rng.integers(0, max(k // 2, 1), size=(W, k)).astype(np.int32)
+            vals = rng.integers(-3, 4, size=(W, k, row_len)).astype(np.float32)      # sums of repeats are exact
+            (g.step_sparse if op == "sparse" else g.local_step_sparse)(dev(idx) if k else None,
+                                                                       dev(vals) if k else None, row_len)
+            (o.step_sparse if op == "sparse" else o.local_step_sparse)(idx, vals, row_len)
+            m["collapsed"], m["sparse_ever"] = False, True        # a sparse step expands the state first
+            if o.steps_since_sync == 0:
+                averaged_by_sync()
+        elif op == "sync":
+            g.sync(); o.sync()
+            if s_before > 0:
+                averaged_by_sync()
+        elif op == "lazy":
+            m["lazy"] = not m["lazy"]
+            g.set_lazy_replicas(m["lazy"])
+            if not m["lazy"]:
+                m["collapsed"] = False                 # switching it off expands the state
+        elif op == "materialize":
+            g.materialize(); m["collapsed"] = False
+        elif op == "coalesce":
+            m["coalesce"] = not m["coalesce"]
+            g.set_sparse_coalesce(m["coalesce"])
+        elif op == "resume":                           # as after restoring a checkpoint into the same arrays
+            g.materialize()
+            g.set_counters(*g.counters())
+            m["collapsed"], m["sparse_only"] = False, False
+            m["dirty_known"] = o.steps_since_sync == 0          # the rows touched before a resume are forgotten
+        elif op == "periods":
+            n_p = int(rng.integers(1, 3))
+            g.run_periods_gen(n_p)
+            for _ in range(n_p * H):
+                o.step_gen()
+            m["collapsed"], m["sparse_only"] = m["lazy"], True
+        elif op == "diag":
+            got, want = g.diagnostics(), o.diagnostics()
+            for k in range(3):
+                assert abs(got[k] - want[k]) <= 2e-5 * max(want[k], 1e-3 * want[0]), (log, k, got, want)
+        elif op == "dirty":
+            if m["dirty_known"]:
+                assert np.array_equal(g.dirty_rows(), o.dirty_rows()), log
+        elif op == "tile":
+            g.set_tile(int(rng.choice([t for t in (1, 2, 4, 8) if W % t == 0])))
+        assert g.counters() == (o.t, o.steps_since_sync), log
+        if o.steps_since_sync == 0:
+            m["dirty_known"] = True
+        torch.cuda.synchronize()
+        gx, ga, gs = host(g.x), host(g.acc), host(g.snap)
+        if m["collapsed"]:                             # defined: row 0 of x and snap
+            gx, ga = np.broadcast_to(gx[:1], gx.shape), np.broadcast_to(gs[None, :], ga.shape)
+        ex = parity.rel_err(gx, o.x, 1.0); eb = parity.rel_err(ga, o.acc, 1e-3); es = parity.rel_err(gs, o.snap, 1e-3)
+        assert ex <= 1e-5 and eb <= 1e-5 and es <= 1e-5, f"after {log}: x {ex:.2e} acc {eb:.2e} snap {es:.2e}"
+
+
 def test_warmup_learning_rate(B):
     W, H, d, T = 4, 4, 4 * 300, 12
     rng = np.random.default_rng(12)
