@@ -16,9 +16,10 @@
  *     laa_last_error() gives a message for the calling thread's last failure.
  *   - "device" pointers are HIP device memory owned by the CALLER (allocated
  *     e.g. through PyTorch).  The library allocates only small bookkeeping
- *     buffers of its own (sparse dirty-row bitmap/list on the first sparse step,
- *     48 KiB of reduction scratch on the first laa_diagnostics), freed by
- *     laa_destroy.
+ *     buffers of its own, on first use (the dirty-row bitmap and list of the
+ *     sparse steps, sort keys and partial rows of the coalescing sparse step,
+ *     48 KiB of reduction scratch for laa_diagnostics, 8 bytes for
+ *     laa_run_periods_gen), freed by laa_destroy.
  *   - All kernels are enqueued on the stream given to laa_attach and return
  *     without waiting, except the getters that copy to host memory, which
  *     synchronise that stream.
@@ -131,11 +132,13 @@ int laa_local_step_dense(laa_handle h, const float *grads);
  * device arrays owned by the caller and read on every generator step.
  *   LAA_GEN_QUADRATIC: g = a_j (x_wj - (xstar_j + off_wj)) + noise_scale * n_wjt
  *   LAA_GEN_NOISE    : g = a_j * n_wjt            (xstar, off unused, may be null)
- * n_wjt ~ N(0,1) from Philox4x32-10: counter (j/4, w, t, 3), key = seed, the four
- * words mapped to u = ((r>>9)+0.5) 2^-23 and Box-Muller pairs (u0,u1),(u2,u3)
- * giving the normals of coordinates 4(j/4)..4(j/4)+3.  off_mode LAA_OFF_PHILOX
- * regenerates off_wj = off_scale * normal from counter (j/4, w, 0, 2) instead
- * of reading an array; LAA_OFF_ARRAY reads off; LAA_OFF_NONE uses zero. */
+ * n_wjt ~ N(0,1) from Philox4x32-10: counter (q mod 2^32, w, t, 3 + 16 (q div 2^32))
+ * with q = j/4, key = seed, the four words mapped to u = ((r>>9)+0.5) 2^-23 and
+ * Box-Muller pairs (u0,u1),(u2,u3) giving the normals of coordinates 4q..4q+3;
+ * j and w are global indices (laa_set_shard), t the 1-based iteration.  off_mode
+ * LAA_OFF_PHILOX regenerates off_wj = off_scale * normal from the same counter
+ * with t = 0 and 2 in place of 3 instead of reading an array; LAA_OFF_ARRAY reads
+ * off; LAA_OFF_NONE uses zero. */
 int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a, const float *xstar,
                       const float *off, int32_t off_mode, float noise_scale, float off_scale);
 
@@ -173,9 +176,8 @@ int laa_generate_gradient(laa_handle h, float *out);
  * row_len floats; worker w updates rows idx[w][0..k) (device int32, [W][k])
  * with values vals [W][k][row_len] (device).  Rows listed by one worker in one
  * call must be distinct unless laa_set_sparse_coalesce is on (different workers
- * may always list the same row).  Rows that
- * are not listed are left untouched, which is exactly Algorithm 3 with a zero
- * gradient there.  Indices outside [0, d/row_len) are skipped and counted
+ * may always list the same row).  Rows that are not listed are left untouched,
+ * which is exactly Algorithm 3 with a zero gradient there.  Indices outside [0, d/row_len) are skipped and counted
  * (laa_get_counters bad_indices).  row_len must be a multiple of 4. */
 int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len);
 
