@@ -333,6 +333,18 @@ def main():
     for _ in range(args.calibrate_copy):          # reads 4d bytes, writes 4d bytes
         B.debug_copy(g.acc[0], g.x[0])
     torch.cuda.synchronize()
+    # The same machine's plain copy rate (one load and one store per thread, the library's copy kernel over one row
+    # of the state), timed the same way: what a streaming kernel can reach here, next to the published peak.
+    copy_gbs = None
+    if d % 4 == 0 and d >= 1 << 22:
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.debug_copy(g.acc[0], g.x[0])
+        c0.record()
+        for _ in range(20):
+            B.debug_copy(g.acc[0], g.x[0])
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 20 * 8 * d / (c0.elapsed_time(c1) * 1e-3) / 1e9
 
     out = {
         "metric": "element-updates/sec and achieved HBM GB/s (% of peak), step+sync, 1 GPU",
@@ -351,7 +363,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(kernel_tag),
                      "kernel": kernel_name, "kernel_ms": kern_ms,
-                     "algorithmic_bytes_per_launch": step_bytes},
+                     "algorithmic_bytes_per_launch": step_bytes, "copy_kernel_gbs_same_run": copy_gbs},
     }
     if not args.no_cpu_baseline and c.kind == "quadratic":
         out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets, args.cpu_procs)
