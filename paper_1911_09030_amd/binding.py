@@ -120,12 +120,14 @@ class SpreadAllocation:
 
     def __init__(self, n_arrays, array_bytes, distance_bytes):
         base, dist = C.c_void_p(), C.c_int64()
+        self._free = lib().laa_spread_free          # kept here: module globals may be gone when __del__ runs at exit
         _check(lib().laa_spread_alloc(int(n_arrays), int(array_bytes), int(distance_bytes), C.byref(base), C.byref(dist)))
         self.base, self.distance_bytes, self.n_arrays = base.value, dist.value, int(n_arrays)
+        self._base_arg = C.c_void_p(base.value)
 
     def close(self):
         if getattr(self, "base", None):
-            lib().laa_spread_free(C.c_void_p(self.base))
+            self._free(self._base_arg)
             self.base = None
 
     __del__ = close
