@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=256)
+    p.add_argument("--steps", type=int, default=None, help="timed iterations (default: the workload's own T; 1024 for c5)")
     p.add_argument("--warmup", type=int, default=16)
     p.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     p.add_argument("--H", type=int, default=0, help="override the sync period (c3 sweep)")
@@ -147,7 +147,7 @@ def main():
             sys.exit(2)
         torch.cuda.set_stream(torch.cuda.Stream(device=dev))     # the default stream cannot be captured
     H = args.H or c.H
-    K, Wm = args.steps, args.warmup
+    K, Wm = (args.steps if args.steps is not None else c.T), args.warmup
     d, W = c.d, c.W
 
     pitch = args.pitch or None
