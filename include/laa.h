@@ -101,8 +101,9 @@ int laa_set_tile(laa_handle h, int32_t workers_per_batch);
  * there for every worker: per column one sync period moves 2W floats less on the averaging pass
  * and 2(W-1) floats less on the pass after it.  While the state is collapsed, rows 1..W-1 of x
  * and all rows of acc are stale; call laa_materialize before reading them (the library does so
- * itself before a sparse step, an Algorithm 1/2 step, or when the option is switched off).
- * Results are bit-identical to the default. */
+ * itself before a sparse step, an Algorithm 2 step, or when the option is switched off).
+ * Algorithm 1 has a single iterate: with this option it is kept in row 0 of x and in snap
+ * throughout.  Results are bit-identical to the default. */
 int laa_set_lazy_replicas(laa_handle h, int32_t on);
 int laa_materialize(laa_handle h);
 

@@ -202,7 +202,9 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
         return fail(LAA_EMODE, "this update rule runs through laa_step_* only");
     if (!adagrad && h->s >= h->H)
         return fail(LAA_ESYNCDUE, "%d local steps since the last sync (H=%d): call laa_sync", h->s, h->H);
-    if (h->algo != LAA_ALGO_LOCAL_ADAALTER && (rc = materialize(h)) != LAA_OK) return rc;
+    // Algorithm 2 steps every worker's own row; Algorithm 1 has one iterate, which stays collapsed with lazy replicas
+    const bool adagrad_row0 = adagrad && h->lazy;
+    if (h->algo != LAA_ALGO_LOCAL_ADAALTER && !adagrad_row0 && (rc = materialize(h)) != LAA_OK) return rc;
 
     laa::StepArgs a{};
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
@@ -223,7 +225,7 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     a.off_source = kind == STEP_DENSE ? laa::OFFSET_NONE : h->off_mode;
     a.sync = adagrad || (allow_fused_sync && h->s + 1 == h->H);
     a.collapsed_in = h->collapsed;
-    a.collapsed_out = a.sync && h->lazy && h->algo == LAA_ALGO_LOCAL_ADAALTER;
+    a.collapsed_out = a.sync && h->lazy && h->algo != LAA_ALGO_LOCAL_SGD;
     a.algo = h->algo;
     a.wt = h->wt;
     a.split = h->split;

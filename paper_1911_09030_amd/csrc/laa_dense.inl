@@ -293,9 +293,11 @@ __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
 
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
 // shared iterate kept in every worker's row.  Algorithm 2 (Local SGD): y = x - eta G per worker.
-template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
+// ROW0 (Algorithm 1 with lazy replicas): the one iterate is read from and written to row 0 of x only, B2 to snap only.
+template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC, bool ROW0>
 __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j)
 {
+    static_assert(!ROW0 || ALGO == ALGO_DIST_ADAGRAD, "only Algorithm 1 has a single iterate");
     Pack<VEC> av, xs;
     if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
     if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
@@ -306,8 +308,11 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
     for (int32_t w0 = 0; w0 < a.W; w0 += WT) {
         Pack<VEC> xv[WT], gv[WT];
 #pragma unroll
-        for (int i = 0; i < WT; ++i) xv[i] = ld<VEC, NT_LD>(a.x + (int64_t)(w0 + i) * a.pitch + j);
-        if (w0 == 0) x0 = xv[0];
+        for (int i = 0; i < WT; ++i) {
+            if constexpr (ROW0) xv[i] = (w0 == 0 && i == 0) ? ld<VEC, false>(a.x + j) : x0;
+            else xv[i] = ld<VEC, NT_LD>(a.x + (int64_t)(w0 + i) * a.pitch + j);
+            if (w0 == 0 && i == 0) x0 = xv[0];
+        }
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
             gv[i] = gradient<VEC, GS, OS>(a, j, (int64_t)(w0 + i) * a.pitch + j, w0 + i, xv[i], av, xs);
@@ -336,9 +341,13 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
             b2.v[e] = fmaf(g, g, b2.v[e]);
             x0.v[e] = x0.v[e] - (a.eta * g) / sqrtf(b2.v[e] + a.eps2);
         }
-        for (int32_t w = 0; w < a.W; ++w) {
-            st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, x0);
-            st<VEC, NT_ST>(a.acc + (int64_t)w * a.pitch + j, b2);
+        if constexpr (ROW0) {
+            st<VEC, false>(a.x + j, x0);
+        } else {
+            for (int32_t w = 0; w < a.W; ++w) {
+                st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, x0);
+                st<VEC, NT_ST>(a.acc + (int64_t)w * a.pitch + j, b2);
+            }
         }
         st<VEC, false>(a.snap + j, b2);
     } else if constexpr (SYNC) {
@@ -348,12 +357,12 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
     }
 }
 
-template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC>
+template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC, bool ROW0 = false>
 __global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
 {
     int64_t j;
     int32_t w_begin, w_end;
-    if (block_work<VEC, false>(a.d, a.W, &j, &w_begin, &w_end)) baseline_body<VEC, WT, GS, OS, ALGO, SYNC>(a, j);
+    if (block_work<VEC, false>(a.d, a.W, &j, &w_begin, &w_end)) baseline_body<VEC, WT, GS, OS, ALGO, SYNC, ROW0>(a, j);
 }
 
 // Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
@@ -476,7 +485,10 @@ static inline hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t
             LAA_STEP(false, false, false, false, false);
         }
     } else if (a.algo == ALGO_DIST_ADAGRAD) {
-        hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(DBLOCK), 0, s, a);
+        if (a.collapsed_out)
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true, true>), grid, dim3(DBLOCK), 0, s, a);
+        else
+            hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_DIST_ADAGRAD, true>), grid, dim3(DBLOCK), 0, s, a);
     } else {
         if (a.sync)
             hipLaunchKernelGGL((baseline_kernel<VEC, WT, GS, OS, ALGO_LOCAL_SGD, true>), grid, dim3(DBLOCK), 0, s, a);

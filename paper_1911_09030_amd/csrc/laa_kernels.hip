@@ -459,7 +459,9 @@ hipError_t launch_step(const StepArgs &a_in, hipStream_t s)
     if (a.d <= 0 || a.W <= 0 || a.wt <= 0 || a.W % a.wt != 0 || !layout_ok(a.d, a.pitch, a.vec4)) return hipErrorInvalidValue;
     // one worker per block only for the plain Local AdaAlter step (no averaging in the same pass)
     a.split = a.split && a.vec4 && !a.sync && !a.grad_out && !a.collapsed_in && a.algo == ALGO_LOCAL_ADAALTER && a.W > 1;
-    if (a.algo != ALGO_LOCAL_ADAALTER && (a.collapsed_in || a.collapsed_out)) return hipErrorInvalidValue;
+    // Algorithm 1 keeps one iterate: with lazy replicas it lives in row 0 of x and in snap throughout
+    if (a.algo == ALGO_LOCAL_SGD && (a.collapsed_in || a.collapsed_out)) return hipErrorInvalidValue;
+    if (a.algo == ALGO_DIST_ADAGRAD && a.collapsed_in && !a.collapsed_out) return hipErrorInvalidValue;
     if (a.collapsed_out && !a.sync) return hipErrorInvalidValue;
     if (a.split) a.wt = 1;
     dim3 grid;

@@ -924,13 +924,19 @@ def test_adagrad_and_local_sgd_variants(B, W, d):
     H, T = 3, 9
     rng = np.random.default_rng(13)
     Gs = [rng.standard_normal((W, d)).astype(np.float32) for _ in range(T)]
+    import torch
     o = Oracle(d, W, 1, 0.3, 0.1, 0.0); o.init_state()
     g = B.LocalAdaAlter(d, W, 1, 0.3, 0.1, b0=0.0); g.set_algorithm(B.ALGO_DIST_ADAGRAD); g.init_state()
+    z = B.LocalAdaAlter(d, W, 1, 0.3, 0.1, b0=0.0); z.set_algorithm(B.ALGO_DIST_ADAGRAD); z.set_lazy_replicas(True)
+    z.init_state()                      # the single iterate of Algorithm 1 kept in row 0 of x and in snap
     sc = parity.Scale(o)
     for G in Gs:
-        o.adagrad_step_dense(G); g.step_dense(dev(G)); sc.update(o)
+        o.adagrad_step_dense(G); g.step_dense(dev(G)); z.step_dense(dev(G)); sc.update(o)
     assert parity.rel_err(host(g.x), o.x, 1e-3, sc.s) <= parity.FULL_RUN
     assert parity.rel_err(host(g.snap), o.snap, 1e-3) <= parity.FULL_RUN
+    z.materialize()
+    torch.cuda.synchronize()
+    assert torch.equal(z.x, g.x) and torch.equal(z.acc, g.acc) and torch.equal(z.snap, g.snap)
     o = Oracle(d, W, H, 0.3, 0.1); o.init_state()
     g = B.LocalAdaAlter(d, W, H, 0.3, 0.1); g.set_algorithm(B.ALGO_LOCAL_SGD); g.init_state()
     sc = parity.Scale(o)
