@@ -116,8 +116,12 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3;
 }
 
-// u = ((r >> 9) + 0.5) * 2^-23: 23 random bits, never 0 or 1, exact in fp32
-__device__ __forceinline__ float u01(uint32_t r) { return fmaf((float)(r >> 9), 0x1p-23f, 0x1p-24f); }
+// u = ((r >> 9) + 0.5) * 2^-23: 23 random bits, never 0 or 1, exact in fp32.  Two operations: the funnel shift
+// (0x7F : r) >> 9 is the bit pattern of 1 + (r >> 9) 2^-23 in [1, 2), and subtracting 1 - 2^-24 from it is exact.
+__device__ __forceinline__ float u01(uint32_t r)
+{
+    return __uint_as_float(__builtin_amdgcn_alignbit(0x7Fu, r, 9u)) - 0x1.fffffep-1f;
+}
 
 // Four standard normals for the coordinates 4*qa .. 4*qa+3 of worker w at iteration word t on a stream.
 // Box-Muller on (u0,u1) and (u2,u3).
