@@ -37,7 +37,7 @@ def say(*a):
     print(*a, flush=True)
 
 
-# a few blocks of 256 threads x 4 coordinates plus a ragged tail
+# many thread blocks (64 threads x 4 coordinates each) plus a ragged tail
 D_SMALL = 4 * (256 * 9 + 37)
 
 
