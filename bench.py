@@ -306,23 +306,34 @@ def main():
     # the dominant kernel is the plain step: not the averaging one ((i+1) % H == 0) and, with lazy replicas, not the
     # one right after it (i % H == 0), which reads the collapsed state
     kernel_name = kernel_tag.rsplit("_", 1)[0]
-    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not (lazy and i % H == 0)]
+    # timed iteration i is iteration t_first + i of the run; the warm-up ends on a period boundary, so iteration i
+    # averages when (i + 1) % H == 0, and reads a collapsed state when the iteration before it averaged
+    after_sync = [lazy and i % H == 0 and t_first + i > 1 for i in range(K)]
+    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not after_sync[i]]
     if not plain and c.kind != "embedding":
-        # H = 1 (or H = 2 with lazy replicas): no plain step exists, the averaging step is the dominant kernel.  It
-        # reads the state (collapsed when the previous iteration averaged too), the inputs, and writes the means.
+        # No plain step among the timed iterations (H = 1, H = 2 with lazy replicas, or very few iterations): the
+        # dominant kernel is the averaging step if there is one, else the step that reads the collapsed state.
         inputs = step_bytes // d - (16 * W + 4)
-        state_in = 8 if (lazy and H == 1) else 8 * W + 4
-        state_out = 8 if lazy else 8 * W + 4
-        step_bytes = (state_in + inputs + state_out) * d
-        kernel_tag += "_sync"
-        kernel_name += " (averaging step)"
-        plain = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
-    plain = plain or per_step_ms
+        sync_idx = [i for i in range(K) if (i + 1) % H == 0]
+        if sync_idx:            # reads the state (collapsed if the iteration before averaged too), writes the means
+            state_in = 8 if after_sync[sync_idx[-1]] else 8 * W + 4
+            state_out = 8 if lazy else 8 * W + 4
+            step_bytes = (state_in + inputs + state_out) * d
+            kernel_tag += "_sync"
+            kernel_name += " (averaging step)"
+            plain = [per_step_ms[i] for i in sync_idx if after_sync[i] == after_sync[sync_idx[-1]]]
+        else:                   # reads row 0 of x, snap and the inputs, writes every worker's rows
+            step_bytes = (8 + inputs + 8 * W) * d
+            kernel_tag += "_after_sync"
+            kernel_name += " (step after an averaging)"
+            plain = per_step_ms
+    if not plain:
+        plain = per_step_ms
     if args.graph:
         plain, step_bytes = per_step_ms, graph_step_bytes
         kernel_tag += "_graph"
         kernel_name += " (average over the iterations of a replayed period)"
-    post_sync = [per_step_ms[i] for i in range(K) if lazy and i % H == 0 and (i + 1) % H != 0]
+    post_sync = [per_step_ms[i] for i in range(K) if after_sync[i] and (i + 1) % H != 0]
     sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
     kern_ms = sum(plain) / len(plain)
     achieved = step_bytes / (kern_ms * 1e-3) / 1e9
