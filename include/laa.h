@@ -16,8 +16,9 @@
  *     laa_last_error() gives a message for the calling thread's last failure.
  *   - "device" pointers are HIP device memory owned by the CALLER (allocated
  *     e.g. through PyTorch).  The library allocates only small bookkeeping
- *     buffers of its own, on first use (the dirty-row bitmap and list of the
- *     sparse steps, sort keys and partial rows of the coalescing sparse step,
+ *     buffers of its own, on first use (the dirty-row bitmap of the sparse
+ *     steps; the row list of laa_sync after sparse steps and of
+ *     laa_get_dirty_rows; sort keys and partial rows of the coalescing sparse step,
  *     48 KiB of reduction scratch for laa_diagnostics, 8 bytes for
  *     laa_run_periods_gen), freed by laa_destroy.
  *   - All kernels are enqueued on the stream given to laa_attach and return
@@ -196,6 +197,17 @@ int laa_set_sparse_coalesce(laa_handle h, int32_t on);
  * no step since the last sync is a no-op; an early call (fewer than H steps) is
  * allowed and restarts t' at 1. */
 int laa_sync(laa_handle h);
+
+/* laa_sync for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same result bit for bit, but the scratch of the averaging after sparse
+ * steps (the ascending list of touched rows, its length, the block counts of the bitmap compaction) lives in
+ * a static device array of the library, 4 MiB + 512 bytes per GPU, instead of buffers that laa_sync and
+ * laa_get_dirty_rows allocate when they first need them.  Calls no hipMalloc / hipFree; the table may have at
+ * most 1 048 576 rows (LAA_EINVAL beyond: nothing is enqueued and nothing changes, use laa_sync).  The
+ * handle's device must be the current one.  Every call on a GPU uses that GPU's one array: calls whose
+ * kernels can overlap (handles on different streams or threads) race; calls on one stream are ordered and
+ * need nothing cleared in between.  A dense averaging needs no scratch and runs exactly as in laa_sync. */
+int laa_sync_static(laa_handle h);
 
 /* One whole iteration of Algorithm 3: the local step and, when it is the H-th
  * since the last sync, the averaging, fused into one pass over the state. */

@@ -22,7 +22,7 @@ ALGO_LOCAL_ADAALTER, ALGO_DIST_ADAGRAD, ALGO_LOCAL_SGD = 0, 1, 2
 EXPORTS = [
     "laa_last_error", "laa_create", "laa_destroy", "laa_set_b0", "laa_set_warmup", "laa_set_algorithm",
     "laa_set_tile", "laa_set_lazy_replicas", "laa_set_sparse_coalesce", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
-    "laa_local_step_gen", "laa_run_periods_gen", "laa_get_replay_count", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_step_dense",
+    "laa_local_step_gen", "laa_run_periods_gen", "laa_get_replay_count", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_sync_static", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_set_shard", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
     "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
 ]
@@ -66,6 +66,7 @@ def lib():
         "laa_generate_gradient": [vp, vp],
         "laa_local_step_sparse": [vp, vp, vp, i32, i32],
         "laa_sync": [vp],
+        "laa_sync_static": [vp],
         "laa_step_dense": [vp, vp],
         "laa_step_gen": [vp],
         "laa_step_sparse": [vp, vp, vp, i32, i32],
@@ -295,6 +296,9 @@ class LocalAdaAlter:
 
     def sync(self):
         _check(self.L.laa_sync(self.h))
+
+    def sync_static(self):
+        _check(self.L.laa_sync_static(self.h))
 
     # queries -------------------------------------------------------------------------------
     def counters(self, with_bad=False):

@@ -66,6 +66,16 @@ struct laa_ctx {
     int64_t replays = 0;                  // periods run by graph replay so far
 };
 
+// Scratch of laa_sync_static: the row list, its length and the block counts of the bitmap compaction, for tables of
+// up to STATIC_MAX_ROWS rows.  One copy per GPU, held until the process ends; its address on a device comes from
+// hipGetSymbolAddress (the array's name is not a device address in host code).
+static constexpr int64_t STATIC_MAX_ROWS = 1 << 20;
+static constexpr size_t STATIC_LIST_BYTES = (size_t)STATIC_MAX_ROWS * sizeof(int32_t);
+static constexpr size_t STATIC_COUNT_AT = STATIC_LIST_BYTES;              // one uint32
+static constexpr size_t STATIC_SCAN_AT = STATIC_LIST_BYTES + 256;         // one uint32 per 1024 bitmap words, + 1
+static constexpr size_t STATIC_SCRATCH_BYTES = STATIC_SCAN_AT + 256;      // 33 words needed at the maximum
+static __device__ __align__(256) unsigned char laa_static_scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[256] = "";
@@ -82,6 +92,28 @@ int fail(int code, const char *fmt, ...)
 int hip_fail(hipError_t e, const char *what)
 {
     return fail(LAA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Device address of laa_static_scratch on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mutex;
+unsigned char *g_static_ptr[MAX_DEVICES] = {};
+
+int static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(LAA_EINVAL, "device %d is outside the %d this library keeps scratch for", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(laa_static_scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(static scratch)");
+        g_static_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_static_ptr[dev];
+    return LAA_OK;
 }
 
 bool aligned(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
@@ -142,15 +174,9 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     const int64_t n_rows = h->d / row_len;
     if (n_rows > 0x7fffffffLL) return fail(LAA_EINVAL, "more than 2^31-1 rows");
     const int64_t nw = n_dirty_words(n_rows);
-    const int64_t nblk = (nw + 1023) / 1024;
     hipError_t e;
     const char *what = "hipMalloc dirty bitmap";
-    if ((e = hipMalloc(&h->dirty, nw * sizeof(uint32_t))) == hipSuccess) {
-        what = "hipMalloc dirty list";
-        e = hipMalloc(&h->dirty_list, n_rows * sizeof(int32_t));
-    }
-    if (e == hipSuccess) { what = "hipMalloc dirty count"; e = hipMalloc(&h->dirty_count, sizeof(uint32_t)); }
-    if (e == hipSuccess) { what = "hipMalloc scan scratch"; e = hipMalloc(&h->scan_scratch, (nblk + 1) * sizeof(uint32_t)); }
+    e = hipMalloc(&h->dirty, nw * sizeof(uint32_t));
     if (e == hipSuccess) { what = "hipMalloc bad-index counter"; e = hipMalloc(&h->bad, sizeof(unsigned long long)); }
     if (e == hipSuccess) { what = "clear dirty bitmap"; e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream); }
     if (e == hipSuccess) {
@@ -164,6 +190,26 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     h->n_rows = n_rows;
     h->row_len = row_len;
     config_changed(h);
+    return LAA_OK;
+}
+
+// The handle's own row list for laa_sync and laa_get_dirty_rows (one int32 per table row, the count and the
+// compaction's block counts), allocated when one of them first needs it; laa_sync_static never does.
+int ensure_row_list(laa_ctx *h)
+{
+    if (h->dirty_list) return LAA_OK;
+    hipError_t e;
+    const char *what = "hipMalloc dirty list";
+    e = hipMalloc(&h->dirty_list, h->n_rows * sizeof(int32_t));
+    if (e == hipSuccess) { what = "hipMalloc dirty count"; e = hipMalloc(&h->dirty_count, sizeof(uint32_t)); }
+    if (e == hipSuccess) { what = "hipMalloc scan scratch"; e = hipMalloc(&h->scan_scratch, (size_t)laa::compact_scratch_words(h->n_rows) * sizeof(uint32_t)); }
+    if (e != hipSuccess) {
+        if (h->dirty_list) (void)hipFree(h->dirty_list);
+        if (h->dirty_count) (void)hipFree(h->dirty_count);
+        if (h->scan_scratch) (void)hipFree(h->scan_scratch);
+        h->dirty_list = nullptr; h->dirty_count = nullptr; h->scan_scratch = nullptr;
+        return hip_fail(e, what);
+    }
     return LAA_OK;
 }
 
@@ -607,7 +653,9 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     return LAA_OK;
 }
 
-int laa_sync(laa_handle h)
+// Synchronize.  static_scratch: the dirty-row list and the compaction's counters live in laa_static_scratch
+// instead of the handle's own buffers.
+static int sync_impl(laa_handle h, bool use_static)
 {
     int rc = check_ready(h);
     if (rc != LAA_OK) return rc;
@@ -616,9 +664,28 @@ int laa_sync(laa_handle h)
     hipError_t e;
     const bool x_only = h->algo == LAA_ALGO_LOCAL_SGD;
     if (h->dirty && h->sparse_only_since_sync && !x_only) {
-        e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
+        int32_t *list = nullptr;
+        uint32_t *count = nullptr, *scan = nullptr;
+        if (use_static) {
+            if (h->n_rows > STATIC_MAX_ROWS)
+                return fail(LAA_EINVAL, "the table has %lld rows; laa_sync_static holds the list of at most %lld (use laa_sync)",
+                            (long long)h->n_rows, (long long)STATIC_MAX_ROWS);
+            if ((size_t)laa::compact_scratch_words(h->n_rows) * sizeof(uint32_t) > STATIC_SCRATCH_BYTES - STATIC_SCAN_AT)
+                return fail(LAA_EINVAL, "the compaction's block counts do not fit the static scratch");
+            unsigned char *base = nullptr;
+            if ((rc = static_scratch(&base)) != LAA_OK) return rc;
+            list = reinterpret_cast<int32_t *>(base);
+            count = reinterpret_cast<uint32_t *>(base + STATIC_COUNT_AT);
+            scan = reinterpret_cast<uint32_t *>(base + STATIC_SCAN_AT);
+        } else {
+            if ((rc = ensure_row_list(h)) != LAA_OK) return rc;
+            list = h->dirty_list; count = h->dirty_count; scan = h->scan_scratch;     // only now allocated for sure
+        }
+        // every word the kernels read from the scratch is written by an earlier kernel of the same call (block counts,
+        // their scan, the count, the first `count` list entries): nothing has to start at zero
+        e = laa::launch_compact_dirty(h->dirty, h->n_rows, list, count, scan, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
-        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, h->dirty_list, h->dirty_count, h->stream);
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, list, count, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
         const bool collapse = h->lazy && !x_only;
@@ -632,6 +699,9 @@ int laa_sync(laa_handle h)
     h->sparse_only_since_sync = true;
     return clear_dirty(h);
 }
+
+int laa_sync(laa_handle h) { return sync_impl(h, false); }
+int laa_sync_static(laa_handle h) { return sync_impl(h, true); }
 
 int laa_step_sparse(laa_handle h, const int32_t *idx, const float *vals, int32_t k, int32_t row_len)
 {
@@ -678,6 +748,7 @@ int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n)
     if (cap < 0 || (cap > 0 && !out)) return fail(LAA_EINVAL, "bad out/cap");
     *n = 0;
     if (!h->dirty) return LAA_OK;
+    if ((rc = ensure_row_list(h)) != LAA_OK) return rc;
     hipError_t e = laa::launch_compact_dirty(h->dirty, h->n_rows, h->dirty_list, h->dirty_count, h->scan_scratch, h->stream);
     if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
     uint32_t cnt = 0;

@@ -75,7 +75,8 @@ int64_t coalesce_partial_rows(int32_t W, int32_t k);
 hipError_t launch_sort_rows(const int32_t *idx, uint64_t *keys, int32_t W, int32_t k, int64_t n_rows, hipStream_t s);
 // Row-sparse step on sorted lists: entries of one worker that list the same row are added up first.
 hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s);
-// bitmap -> ascending row list (device) + count (device); scratch holds one uint32 per 1024 bitmap words (+1)
+// bitmap -> ascending row list (device) + count (device); scratch holds compact_scratch_words(n_rows) uint32
+int64_t compact_scratch_words(int64_t n_rows);
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s);
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,

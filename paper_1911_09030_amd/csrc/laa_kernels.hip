@@ -599,9 +599,16 @@ hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+int64_t compact_scratch_words(int64_t n_rows)
+{
+    const int64_t n_words = (n_rows + 31) / 32;
+    return (n_words + WORDS_PER_BLOCK - 1) / WORDS_PER_BLOCK + 1;
+}
+
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s)
 {
+    if (!dirty || !list || !count || !scratch) return hipErrorInvalidValue;
     const int64_t n_words = (n_rows + 31) / 32;
     const int64_t nb = (n_words + WORDS_PER_BLOCK - 1) / WORDS_PER_BLOCK;
     if (nb <= 0 || nb > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -615,6 +622,7 @@ hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, in
                             const int32_t *list, const uint32_t *count, hipStream_t s)
 {
     if (W <= 0 || wt <= 0 || W % wt != 0 || row_len <= 0 || row_len % 4 != 0) return hipErrorInvalidValue;
+    if (!x || !acc || !snap || !list || !count) return hipErrorInvalidValue;
     const dim3 grid(2048), block(BLOCK);
     switch (wt) {               // the same batches as the dense mean: one order of the worker-axis sum everywhere
     case 8: hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
