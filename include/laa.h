@@ -188,7 +188,9 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
  * Algorithm 3 is taken once with that sum (so acc grows by the square of the sum).  Each worker's list
  * is sorted on the device first, which limits k to 8192 rows per worker and step (LAA_EINVAL beyond)
  * and costs a small extra pass; lists without repeats give bit-identical results either way.
- * Off by default. */
+ * The first coalescing step (and the first after row_len grew) allocates the sort keys and the partial rows
+ * for that limit (8 W KiB and 2 KiB W row_len), which waits for the device like any hipMalloc; later
+ * steps allocate nothing.  Off by default. */
 int laa_set_sparse_coalesce(laa_handle h, int32_t on);
 
 /* Algorithm 3, Synchronize: x[w] and acc[w] become the means over w, snap the
@@ -242,10 +244,17 @@ int laa_get_dirty_rows(laa_handle h, int32_t *out, int64_t cap, int64_t *n);
  * scratch buffer on first use. */
 int laa_diagnostics(laa_handle h, double *out);
 
-/* Bytes the method itself had to move for everything enqueued so far
- * (x, acc read+write per element-update, snap and generator arrays once per
- * column-step, literal sync traffic), for bandwidth accounting. */
-int laa_bytes_moved(laa_handle h, uint64_t *algorithmic_bytes);
+/* Byte counters for bandwidth accounting, for everything enqueued since laa_init_state; either pointer may be null.
+ *   *moved_bytes:   what the launches read and write: x, acc of every worker and snap once per column, the
+ *                   generator's arrays or the explicit gradients, the averaged state; with lazy replicas the
+ *                   collapsed state counts as what it is (row 0 of x and snap, 8 bytes per column), and so do
+ *                   laa_materialize, the sort keys of the coalescing step and the rows averaged after sparse steps.
+ *                   Dividing it by the elapsed time gives the rate the memory system delivered.
+ *   *literal_bytes: the same iterations as Algorithm 3 spells them out, a local step over full replicas
+ *                   (16 W + 4 bytes per column and the gradient's inputs) and a separate Synchronize pass
+ *                   (16 W + 4) whenever one averaged: the traffic that fusing and lazy replicas save is still in it.
+ * After sparse steps the number of averaged rows is read from the device: the call then synchronises the stream. */
+int laa_bytes_moved(laa_handle h, uint64_t *moved_bytes, uint64_t *literal_bytes);
 
 /* Optional allocation helper for the state arrays (the library never needs it: any device memory
  * can be attached).  Allocates n_arrays arrays of array_bytes each whose starts are distance_bytes

@@ -78,7 +78,7 @@ def lib():
         "laa_set_shard": [vp, i64, i32],
         "laa_get_dirty_rows": [vp, vp, i64, C.POINTER(i64)],
         "laa_diagnostics": [vp, C.POINTER(C.c_double)],
-        "laa_bytes_moved": [vp, C.POINTER(u64)],
+        "laa_bytes_moved": [vp, C.POINTER(u64), C.POINTER(u64)],
         "laa_spread_alloc": [i32, i64, i64, C.POINTER(vp), C.POINTER(i64)],
         "laa_spread_free": [vp],
         "laa_debug_philox": [vp, vp, vp],
@@ -337,10 +337,12 @@ class LocalAdaAlter:
         _check(self.L.laa_diagnostics(self.h, out))
         return tuple(out)
 
-    def bytes_moved(self):
-        b = C.c_uint64()
-        _check(self.L.laa_bytes_moved(self.h, C.byref(b)))
-        return b.value
+    def bytes_moved(self, literal=False):
+        """Bytes the launches so far read and wrote; literal=True: (moved, literal) with the traffic of the same
+        iterations as separate step and Synchronize passes over full replicas."""
+        b, lit = C.c_uint64(), C.c_uint64()
+        _check(self.L.laa_bytes_moved(self.h, C.byref(b), C.byref(lit)))
+        return (b.value, lit.value) if literal else b.value
 
 
 def debug_philox(ctr, key):

@@ -46,10 +46,11 @@ struct laa_ctx {
     float *partials = nullptr;        // partial sums of rows listed many times
     int64_t partial_cap = 0;          // floats allocated
     uint32_t *dirty_count = nullptr, *scan_scratch = nullptr;
-    unsigned long long *bad = nullptr;
+    unsigned long long *bad = nullptr;    // [0] out-of-range indices skipped, [1] rows averaged by sparse syncs
     double *diag_scratch = nullptr;   // block partials + results of laa_diagnostics
     bool sparse_only_since_sync = true;   // every step since the last sync was a sparse one
-    uint64_t bytes = 0;
+    uint64_t bytes = 0;                   // bytes the launches enqueued so far read and write (collapsed state counted as such)
+    uint64_t bytes_literal = 0;           // the same iterations as separate step and Synchronize passes over full replicas
     // replayed periods (laa_run_periods_gen): one captured graph per state the period can start in
     struct PeriodGraph {
         hipGraph_t graph = nullptr;
@@ -58,7 +59,7 @@ struct laa_ctx {
         bool warmed = false;              // an eager period of this kind has run (kernels loaded) at that epoch
         uint64_t warmed_epoch = 0;
         bool end_collapsed = false;
-        uint64_t bytes = 0;               // algorithmic bytes of one period
+        uint64_t bytes = 0, bytes_literal = 0;   // byte counters of one period
     } period[2];                          // [0]: starts from full replicas, [1]: from the collapsed state
     uint64_t epoch = 1;                   // bumped whenever something a captured kernel argument depends on changes
     uint32_t *t_dev = nullptr;            // device word: iteration count at the start of the period being replayed
@@ -177,11 +178,11 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     hipError_t e;
     const char *what = "hipMalloc dirty bitmap";
     e = hipMalloc(&h->dirty, nw * sizeof(uint32_t));
-    if (e == hipSuccess) { what = "hipMalloc bad-index counter"; e = hipMalloc(&h->bad, sizeof(unsigned long long)); }
+    if (e == hipSuccess) { what = "hipMalloc sparse counters"; e = hipMalloc(&h->bad, 2 * sizeof(unsigned long long)); }
     if (e == hipSuccess) { what = "clear dirty bitmap"; e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream); }
     if (e == hipSuccess) {
-        what = "clear bad-index counter";
-        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 2, h->stream);
+        what = "clear sparse counters";
+        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 4, h->stream);
     }
     if (e != hipSuccess) {
         free_sparse(h);                   // all or nothing: the next call starts from scratch
@@ -220,6 +221,7 @@ int materialize(laa_ctx *h)
     hipError_t e = laa::launch_materialize(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "materialize kernel launch");
     h->collapsed = false;
+    h->bytes += (uint64_t)(8 + 8 * h->W - 4) * (uint64_t)h->d;      // reads row 0 of x and snap; writes the other rows of x, all of acc
     return LAA_OK;
 }
 
@@ -280,17 +282,32 @@ int dense_step(laa_handle h, StepKind kind, const float *grads, bool allow_fused
     hipError_t e = laa::launch_step(a, h->stream);
     if (e != hipSuccess) return hip_fail(e, "step kernel launch");
 
+    // byte counters, per column: what this launch moves, and what the same iteration moves as a plain step over full
+    // replicas followed (when it averages) by a separate Synchronize pass
     const uint64_t W = (uint64_t)h->W, d = (uint64_t)h->d;
-    uint64_t col_bytes = 16 * W + 4;                        // x, acc read+write; snap read
-    if (kind == STEP_DENSE) col_bytes += 4 * W;
-    else col_bytes += (h->gen_mode == LAA_GEN_QUADRATIC ? 8 : 4) + (h->off_mode == LAA_OFF_ARRAY ? 4 * W : 0);
-    h->bytes += col_bytes * d;
+    uint64_t inputs = 4 * W;                                // explicit gradients
+    if (kind != STEP_DENSE)
+        inputs = (h->gen_mode == LAA_GEN_QUADRATIC ? 8 : 4) + (h->off_mode == LAA_OFF_ARRAY ? 4 * W : 0);
+    uint64_t moved, literal;
+    if (h->algo == LAA_ALGO_LOCAL_ADAALTER) {
+        const uint64_t in = a.collapsed_in ? 8 : 8 * W + 4;                  // x, acc of every worker and snap, or row 0 and snap
+        const uint64_t out = !a.sync ? 8 * W : a.collapsed_out ? 8 : 8 * W + 4;
+        moved = in + inputs + out;
+        literal = 16 * W + 4 + inputs + (a.sync ? 16 * W + 4 : 0);
+    } else if (adagrad) {                                   // one iterate: x rows and snap in, x, acc rows and snap out
+        moved = (a.collapsed_out ? 8 : 4 * W + 4) + inputs + (a.collapsed_out ? 8 : 8 * W + 4);
+        literal = 4 * W + 4 + inputs + 8 * W + 4;
+    } else {                                                // Local SGD: x rows in and out
+        moved = 8 * W + inputs;
+        literal = 8 * W + inputs + (a.sync ? 8 * W : 0);
+    }
+    h->bytes += moved * d;
+    h->bytes_literal += literal * d;
     h->t += 1;
     h->s += 1;
     h->sparse_only_since_sync = false;
     h->collapsed = a.collapsed_out;
     if (a.sync) {
-        h->bytes += (16 * W + 4) * d;                       // literal sync traffic: read 2W, write 2W+1 floats
         h->s = 0;
         h->sparse_only_since_sync = true;
         rc = clear_dirty(h);
@@ -436,7 +453,9 @@ int laa_init_state(laa_handle h, const float *x0)
     const float b0sq = (float)(h->b0 * h->b0);
     hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "init kernel launch");
-    h->t = 0; h->s = 0; h->bytes = 0; h->sparse_only_since_sync = true; h->collapsed = false;
+    h->t = 0; h->s = 0; h->bytes = 0; h->bytes_literal = 0; h->sparse_only_since_sync = true; h->collapsed = false;
+    if (h->bad && laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad + 1), 0u, 2, h->stream) != hipSuccess)
+        return fail(LAA_EHIP, "clearing the sparse-sync row counter");
     return clear_dirty(h);
 }
 
@@ -521,7 +540,9 @@ int laa_run_periods_gen(laa_handle h, int32_t n_periods)
             // Record the H launches of one period with iteration numbers 1..H relative to the device word, which the
             // last node of the graph advances by H.  Nothing runs during capture; the host state is put back after.
             const int64_t t_saved = h->t, warm_saved = h->warmup_steps;
-            const uint64_t bytes_saved = h->bytes;
+            const uint64_t bytes_saved = h->bytes, literal_saved = h->bytes_literal;
+            const int32_t s_saved = h->s;
+            const bool sparse_only_saved = h->sparse_only_since_sync;
             if ((e = hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
                 return hip_fail(e, "hipStreamBeginCapture");
             h->capturing = true; h->t = 0; h->warmup_steps = 0;
@@ -530,7 +551,10 @@ int laa_run_periods_gen(laa_handle h, int32_t n_periods)
             h->capturing = false; h->t = t_saved; h->warmup_steps = warm_saved;
             pg.end_collapsed = h->collapsed;
             pg.bytes = h->bytes - bytes_saved;
-            h->bytes = bytes_saved;
+            pg.bytes_literal = h->bytes_literal - literal_saved;
+            // nothing ran: put back everything the recorded calls changed on the host, also when recording failed midway
+            h->bytes = bytes_saved; h->bytes_literal = literal_saved;
+            h->s = s_saved; h->sparse_only_since_sync = sparse_only_saved;
             h->collapsed = c != 0;
             e = hipStreamEndCapture(h->stream, &pg.graph);            // always leave capture mode
             if (rc != LAA_OK) { if (pg.graph) (void)hipGraphDestroy(pg.graph); pg.graph = nullptr; return rc; }
@@ -551,6 +575,7 @@ int laa_run_periods_gen(laa_handle h, int32_t n_periods)
             h->t += h->H;
             h->replays += 1;
             h->bytes += pg.bytes;
+            h->bytes_literal += pg.bytes_literal;
             h->collapsed = pg.end_collapsed;
             h->sparse_only_since_sync = true;
             const bool next_in_warmup = h->warmup_steps > 0 && h->t < h->warmup_steps;
@@ -621,16 +646,18 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     a.pad = (float)(h->s + 1) * (float)(h->eps * h->eps);
     hipError_t e;
     if (h->coalesce && k > 0) {
-        const int64_t need = (int64_t)h->W * k;
+        // Sized on first use for the longest list the coalescing step takes, so that no later step allocates: a
+        // step that found its buffers too small would have to free them, and hipFree waits for the device.
+        const int64_t need = (int64_t)h->W * laa::coalesce_max_k();
         if (need > h->sort_cap) {
-            if (h->sort_keys) (void)hipFree(h->sort_keys);        // hipFree waits for the kernels that still use it
+            if (h->sort_keys) (void)hipFree(h->sort_keys);
             h->sort_keys = nullptr; h->sort_cap = 0;
             if ((e = hipMalloc(&h->sort_keys, (size_t)need * sizeof(uint64_t))) != hipSuccess)
                 return hip_fail(e, "hipMalloc sort keys");
             h->sort_cap = need;
         }
-        const int64_t need_p = laa::coalesce_partial_rows(h->W, k) * row_len;
-        if (need_p > h->partial_cap) {
+        const int64_t need_p = laa::coalesce_partial_rows(h->W, laa::coalesce_max_k()) * row_len;
+        if (need_p > h->partial_cap) {                      // only when row_len grew (ensure_sparse dropped the old ones)
             if (h->partials) (void)hipFree(h->partials);
             h->partials = nullptr; h->partial_cap = 0;
             if ((e = hipMalloc(&h->partials, (size_t)need_p * sizeof(float))) != hipSuccess)
@@ -643,11 +670,13 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
         a.keys = h->sort_keys;
         if ((e = laa::launch_sparse_step_coalesce(a, h->stream)) != hipSuccess)
             return hip_fail(e, "coalescing sparse step kernel launch");
-        h->bytes += (uint64_t)need * 16;                          // keys written, then read
+        h->bytes += (uint64_t)h->W * (uint64_t)k * 16;             // keys written, then read
+        h->bytes_literal += (uint64_t)h->W * (uint64_t)k * 16;
     } else {
         if ((e = laa::launch_sparse_step(a, h->stream)) != hipSuccess) return hip_fail(e, "sparse step kernel launch");
     }
     h->bytes += (uint64_t)h->W * (uint64_t)k * ((uint64_t)row_len * 24 + 4);
+    h->bytes_literal += (uint64_t)h->W * (uint64_t)k * ((uint64_t)row_len * 24 + 4);
     h->t += 1;
     h->s += 1;
     return LAA_OK;
@@ -685,14 +714,17 @@ static int sync_impl(laa_handle h, bool use_static)
         // their scan, the count, the first `count` list entries): nothing has to start at zero
         e = laa::launch_compact_dirty(h->dirty, h->n_rows, list, count, scan, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
-        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, list, count, h->stream);
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, list, count, h->bad + 1,
+                                  h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
         const bool collapse = h->lazy && !x_only;
         e = laa::launch_mean(h->x, h->acc, h->snap, h->d, h->pitch, h->W, h->vec4, h->wt, x_only,
                              collapse, h->stream);
         if (e != hipSuccess) return hip_fail(e, "mean kernel launch");
-        h->bytes += (uint64_t)(16 * h->W + 4) * (uint64_t)h->d;
+        const uint64_t W = (uint64_t)h->W;
+        h->bytes += (x_only ? 8 * W : 8 * W + (collapse ? 8 : 8 * W + 4)) * (uint64_t)h->d;
+        h->bytes_literal += (x_only ? 8 * W : 16 * W + 4) * (uint64_t)h->d;
         h->collapsed = collapse;
     }
     h->s = 0;
@@ -795,10 +827,19 @@ int laa_diagnostics(laa_handle h, double *out)
     return LAA_OK;
 }
 
-int laa_bytes_moved(laa_handle h, uint64_t *algorithmic_bytes)
+int laa_bytes_moved(laa_handle h, uint64_t *moved_bytes, uint64_t *literal_bytes)
 {
-    if (!h || !algorithmic_bytes) return fail(LAA_EINVAL, "null argument");
-    *algorithmic_bytes = h->bytes;
+    if (!h || (!moved_bytes && !literal_bytes)) return fail(LAA_EINVAL, "null argument");
+    uint64_t sparse_sync = 0;
+    if (h->bad) {                       // rows averaged by sparse syncs are counted on the device
+        unsigned long long rows = 0;
+        hipError_t e = hipMemcpyAsync(&rows, h->bad + 1, sizeof(rows), hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) return hip_fail(e, "reading the sparse-sync row counter");
+        sparse_sync = (uint64_t)rows * (uint64_t)(16 * h->W + 4) * (uint64_t)h->row_len;
+    }
+    if (moved_bytes) *moved_bytes = h->bytes + sparse_sync;
+    if (literal_bytes) *literal_bytes = h->bytes_literal + sparse_sync;
     return LAA_OK;
 }
 

@@ -79,8 +79,9 @@ hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s);
 int64_t compact_scratch_words(int64_t n_rows);
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s);
+// rows_total (may be null): the number of rows averaged is added to it, for byte accounting
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,
-                            const int32_t *list, const uint32_t *count, hipStream_t s);
+                            const int32_t *list, const uint32_t *count, unsigned long long *rows_total, hipStream_t s);
 int32_t diag_scratch_doubles();
 hipError_t launch_diagnostics(const StepArgs &a, double *scratch, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);

@@ -318,21 +318,42 @@ __global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__re
     }
 }
 
-// Synchronize branch restricted to the listed rows; a fixed grid of wavefronts strides over the list,
-// whose length is read from device memory.
+// Synchronize branch restricted to the listed rows.  The length of the list is only known on the device, so a fixed
+// grid of one-wavefront blocks strides over the work items, an item being 256 consecutive floats of a listed row
+// (16 bytes per lane) for all W workers: 2W non-temporal 16-byte loads in flight per lane, 2W + 1 stores.  The row
+// number of the next item is fetched before the current item's loads are waited for.
+#ifndef LAA_ROWS_WAVES_PER_CU
+#define LAA_ROWS_WAVES_PER_CU 16
+#endif
+#ifndef LAA_ROWS_NT
+#define LAA_ROWS_NT true
+#endif
+static constexpr int N_CU = 256;                                     // MI355X
+static constexpr bool ROWS_NT = LAA_ROWS_NT;
+
 template <int WT>
-__global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
-                                                          float *__restrict__ snap, int64_t pitch, int32_t W,
-                                                          int32_t row_len, const int32_t *__restrict__ list,
-                                                          const uint32_t *__restrict__ count)
+__global__ __launch_bounds__(WAVE) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
+                                                         float *__restrict__ snap, int64_t pitch, int32_t W,
+                                                         int32_t row_len, const int32_t *__restrict__ list,
+                                                         const uint32_t *__restrict__ count,
+                                                         unsigned long long *__restrict__ rows_total)
 {
     const uint32_t n = *count;
-    const uint32_t n_waves = gridDim.x * WAVES_PER_BLOCK;
-    const int lane = threadIdx.x % WAVE;
+    if (rows_total && blockIdx.x == 0 && threadIdx.x == 0) *rows_total += n;
+    const uint32_t chunks = (uint32_t)(row_len + WAVE * 4 - 1) / (WAVE * 4);
+    const uint64_t items = (uint64_t)n * chunks;
+    uint64_t it = blockIdx.x;
+    if (it >= items) return;
+    const int lane = threadIdx.x;
     const float fw = (float)W;
-    for (uint32_t i = blockIdx.x * WAVES_PER_BLOCK + threadIdx.x / WAVE; i < n; i += n_waves) {
-        const int64_t col = (int64_t)list[i] * row_len;
-        for (int32_t e = lane * 4; e < row_len; e += WAVE * 4) {
+    int32_t row = list[it / chunks];
+    while (true) {
+        const uint64_t nxt = it + gridDim.x;
+        const bool more = nxt < items;
+        const int32_t row_next = more ? list[nxt / chunks] : 0;
+        const int32_t e = (int32_t)(it % chunks) * (WAVE * 4) + lane * 4;
+        if (e < row_len) {
+            const int64_t col = (int64_t)row * row_len + e;
             Pack<4> sx, sb;
 #pragma unroll
             for (int c = 0; c < 4; ++c) sx.v[c] = sb.v[c] = 0.0f;
@@ -340,8 +361,8 @@ __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x,
                 Pack<4> xv[WT], bv[WT];
 #pragma unroll
                 for (int k = 0; k < WT; ++k) {
-                    xv[k] = ld<4, false>(x + (int64_t)(w0 + k) * pitch + col + e);
-                    bv[k] = ld<4, false>(acc + (int64_t)(w0 + k) * pitch + col + e);
+                    xv[k] = ld<4, ROWS_NT>(x + (int64_t)(w0 + k) * pitch + col);
+                    bv[k] = ld<4, ROWS_NT>(acc + (int64_t)(w0 + k) * pitch + col);
                 }
                 const Pack<4> tx = tree_sum<4, WT>(xv), tb = tree_sum<4, WT>(bv);
 #pragma unroll
@@ -350,11 +371,14 @@ __global__ __launch_bounds__(BLOCK) void mean_rows_kernel(float *__restrict__ x,
 #pragma unroll
             for (int c = 0; c < 4; ++c) { sx.v[c] = sx.v[c] / fw; sb.v[c] = sb.v[c] / fw; }
             for (int32_t w = 0; w < W; ++w) {
-                st<4, false>(x + (int64_t)w * pitch + col + e, sx);
-                st<4, false>(acc + (int64_t)w * pitch + col + e, sb);
+                st<4, ROWS_NT>(x + (int64_t)w * pitch + col, sx);
+                st<4, ROWS_NT>(acc + (int64_t)w * pitch + col, sb);
             }
-            st<4, false>(snap + col + e, sb);
+            st<4, false>(snap + col, sb);
         }
+        if (!more) break;
+        it = nxt;
+        row = row_next;
     }
 }
 
@@ -619,18 +643,20 @@ hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *
 }
 
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,
-                            const int32_t *list, const uint32_t *count, hipStream_t s)
+                            const int32_t *list, const uint32_t *count, unsigned long long *rows_total, hipStream_t s)
 {
     if (W <= 0 || wt <= 0 || W % wt != 0 || row_len <= 0 || row_len % 4 != 0) return hipErrorInvalidValue;
     if (!x || !acc || !snap || !list || !count) return hipErrorInvalidValue;
-    const dim3 grid(2048), block(BLOCK);
+    const dim3 grid(N_CU * LAA_ROWS_WAVES_PER_CU), block(WAVE);
+#define LAA_ROWS(WT) hipLaunchKernelGGL((mean_rows_kernel<WT>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count, rows_total)
     switch (wt) {               // the same batches as the dense mean: one order of the worker-axis sum everywhere
-    case 8: hipLaunchKernelGGL((mean_rows_kernel<8>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
-    case 4: hipLaunchKernelGGL((mean_rows_kernel<4>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
-    case 2: hipLaunchKernelGGL((mean_rows_kernel<2>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
-    case 1: hipLaunchKernelGGL((mean_rows_kernel<1>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count); break;
+    case 8: LAA_ROWS(8); break;
+    case 4: LAA_ROWS(4); break;
+    case 2: LAA_ROWS(2); break;
+    case 1: LAA_ROWS(1); break;
     default: return hipErrorInvalidValue;
     }
+#undef LAA_ROWS
     return hipGetLastError();
 }
 

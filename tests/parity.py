@@ -48,3 +48,22 @@ def assert_state(got_x, got_acc, got_snap, ora, bar, floor_x=FLOOR_X, floor_b=FL
     es = rel_err(got_snap, ora.snap, floor_b)
     assert ex <= bar and eb <= bar and es <= bar, f"{what}: rel err x {ex:.2e} acc {eb:.2e} snap {es:.2e} > {bar:.0e}"
     return ex, eb, es
+
+
+def assert_one_step_generated(got_x, got_acc, x_before, ora, g_ref, S, eta, den, what=""):
+    """One generator-fed step against the oracle, with the bound the arithmetic gives instead of a floor.
+
+    The generated gradient is within 1e-6 S of the oracle's (S = magnitude of its terms, asserted separately), so
+    x' = x - eta g / den is within eta (1e-6 S) / den plus a few roundings of the larger of |x|, |x'|:
+        |dx|   <= 1e-6 (max(|x|, |x'|) + eta S / den)
+    and acc' = acc + g^2 within 2 |g| (1e-6 S) plus one rounding of acc':
+        |dacc| <= 1e-6 (acc' + 2 |g| S)
+    """
+    got_x = np.asarray(got_x, dtype=np.float64)
+    got_acc = np.asarray(got_acc, dtype=np.float64)
+    bx = ONE_STEP * (np.maximum(np.abs(x_before), np.abs(ora.x)) + abs(eta) * S / den)
+    bb = ONE_STEP * (np.abs(ora.acc) + 2 * np.abs(g_ref) * S)
+    rx = float(np.max(np.abs(got_x - ora.x) / bx))
+    rb = float(np.max(np.abs(got_acc - ora.acc) / bb))
+    assert rx <= 1.0 and rb <= 1.0, f"{what}: one generated step is {rx:.2f} (x) and {rb:.2f} (acc) of the 1e-6 bound"
+    return rx, rb

@@ -89,8 +89,10 @@ def test_host_error_paths(L):
     assert L.laa_get_counters(h, C.byref(t), C.byref(s), None) == binding.OK and (t.value, s.value) == (7, 1)
     assert L.laa_set_counters(h, 0, 0) == binding.OK
     b = C.c_uint64(5)
-    assert L.laa_bytes_moved(h, C.byref(b)) == binding.OK and b.value == 0
-    assert L.laa_bytes_moved(h, None) == binding.EINVAL
+    lit = C.c_uint64(5)
+    assert L.laa_bytes_moved(h, C.byref(b), C.byref(lit)) == binding.OK and b.value == 0 and lit.value == 0
+    assert L.laa_bytes_moved(h, None, C.byref(lit)) == binding.OK
+    assert L.laa_bytes_moved(h, None, None) == binding.EINVAL
     assert L.laa_destroy(h) == binding.OK
 
 

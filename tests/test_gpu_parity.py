@@ -509,9 +509,13 @@ def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d, tile):
         err = np.max(np.abs(G_gpu - G_ref) / scale)
         assert err <= 1e-6, f"gradient at t={t}: {err:.2e}"
         Gu = u.generate_gradient()
+        den = np.sqrt(o.snap + (o.steps_since_sync + 1) * 1.0)[None, :]
         g.step_gen(); u.step_dense(Gu); o.step_gen()
         torch.cuda.synchronize()
         assert torch.equal(g.x, u.x) and torch.equal(g.acc, u.acc), f"fused != unfused at t={t}"
+        if t == 1:                   # both sides start from the same state: the bound the arithmetic gives, no floor
+            r = parity.assert_one_step_generated(host(g.x), host(g.acc), x_before, o, G_ref, scale, 0.5, den, "gen t=1")
+            say(f"   one generated step: {r[0]:.2f} (x), {r[1]:.2f} (acc) of the 1e-6 bound")
         bar = 1e-5
         parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, bar, floor_x=1.0, what=f"gen t={t}")
 
@@ -904,6 +908,58 @@ def test_random_call_sequences_follow_the_oracle(B, seed):
         assert ex <= 1e-5 and eb <= 1e-5 and es <= 1e-5, f"after {log}: x {ex:.2e} acc {eb:.2e} snap {es:.2e}"
 
 
+def test_byte_counters(B):
+    """laa_bytes_moved: what the launches move (collapsed state counted as such) and the literal traffic of the same
+    iterations as separate step and Synchronize passes over full replicas."""
+    W, H, d = 8, 4, 4 * 64 * 6
+    rng = np.random.default_rng(3)
+    a, xs = dev(rng.uniform(0.1, 10, d).astype(np.float32)), dev(rng.standard_normal(d).astype(np.float32))
+    inputs = 8                                   # a, xstar once per column
+    plain, lit_step, lit_sync = 16 * W + 4 + inputs, 16 * W + 4 + inputs, 16 * W + 4
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.set_lazy_replicas(True); g.init_state()
+    g.set_generator(B.GEN_QUADRATIC, 1, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    for _ in range(2 * H):
+        g.step_gen()
+    averaging = (8 * W + 4) + inputs + 8         # reads every replica, writes row 0 of x and snap
+    after = 8 + inputs + 8 * W                   # reads row 0 of x and snap, writes every replica
+    moved = ((H - 1) * plain + averaging) + (after + (H - 2) * plain + averaging)
+    literal = 2 * H * lit_step + 2 * lit_sync
+    assert g.bytes_moved(literal=True) == (moved * d, literal * d)
+    g.materialize()                              # reads row 0 of x and snap, writes the other 2W - 1 rows
+    assert g.bytes_moved(literal=True) == ((moved + 8 + 8 * W - 4) * d, literal * d)
+    # the same period without lazy replicas: fusing alone saves the second read of x and acc
+    f = B.LocalAdaAlter(d, W, H, 0.5, 1.0); f.init_state()
+    f.set_generator(B.GEN_QUADRATIC, 1, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    for _ in range(H):
+        f.step_gen()
+    assert f.bytes_moved(literal=True) == (((H - 1) * plain + 16 * W + 8 + inputs) * d, (H * lit_step + lit_sync) * d)
+    f.init_state()                               # counters restart
+    for _ in range(H):
+        f.local_step_gen()
+    f.sync()                                     # unfused: both counters are the literal traffic
+    assert f.bytes_moved(literal=True) == ((H * lit_step + lit_sync) * d,) * 2
+    # H = 1 with lazy replicas: the state stays collapsed, 8 bytes in and 8 bytes out per column
+    h1 = B.LocalAdaAlter(d, W, 1, 0.5, 1.0); h1.set_lazy_replicas(True); h1.init_state()
+    h1.set_generator(B.GEN_QUADRATIC, 1, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    for _ in range(3):
+        h1.step_gen()
+    assert h1.bytes_moved(literal=True) == ((averaging + 2 * (8 + inputs + 8)) * d, 3 * (lit_step + lit_sync) * d)
+    # sparse period: the rows that the averaging touched are counted on the device
+    rows, row_len, k = 100, 8, 10
+    sp = B.LocalAdaAlter(rows * row_len, 4, 2, 0.5, 1.0); sp.init_state()
+    zipf = wl.ZipfRows(rows, 1.1)
+    for t in (1, 2):
+        idx, vals = wl.sparse_step(zipf, 4, k, row_len, 9, t)
+        sp.local_step_sparse(dev(idx), dev(vals), row_len)
+    n_dirty = sp.dirty_rows().size
+    step_b = 2 * 4 * k * (24 * row_len + 4)
+    assert sp.bytes_moved(literal=True) == (step_b, step_b)
+    sp.sync()
+    assert sp.bytes_moved() == step_b + n_dirty * (16 * 4 + 4) * row_len and 0 < n_dirty <= 2 * 4 * k
+    sp.init_state()
+    assert sp.bytes_moved(literal=True) == (0, 0)
+
+
 def test_warmup_learning_rate(B):
     W, H, d, T = 4, 4, 4 * 300, 12
     rng = np.random.default_rng(12)
@@ -947,6 +1003,69 @@ def test_adagrad_and_local_sgd_variants(B, W, d):
         g.local_step_dense(dev(Gs[0]))
 
 
+@pytest.mark.parametrize("algo,mode,off_mode,W,d,lazy", [
+    ("adagrad", "quad", "philox", 8, D_SMALL, False), ("adagrad", "quad", "philox", 8, D_SMALL, True),
+    ("adagrad", "quad", "array", 3, 4 * 300 + 3, False), ("adagrad", "quad", "none", 3, 4 * 300 + 3, True),
+    ("adagrad", "noise", "none", 8, 4 * 64 * 5, True), ("adagrad", "noise", "none", 3, 1001, False),
+    ("adagrad", "quad", "philox", 16, 4 * 333, True),
+    ("sgd", "quad", "philox", 8, D_SMALL, False), ("sgd", "quad", "array", 3, 4 * 300 + 3, False),
+    ("sgd", "noise", "none", 3, 1001, False), ("sgd", "noise", "none", 8, 4 * 64 * 5, True),
+    ("sgd", "quad", "philox", 16, 4 * 333, True)])
+def test_generator_fed_adagrad_and_local_sgd(B, algo, mode, off_mode, W, d, lazy):
+    """Algorithms 1 and 2 with the gradient generated in the kernel, against the oracle's gradient followed by its
+    Algorithm 1 / Algorithm 2 step: each worker's gradient is evaluated at its own iterate with its own random
+    numbers (Algorithm 1: at the one shared iterate, also when that is kept in row 0 only)."""
+    import torch
+    say(f"generator-fed {algo} mode={mode} off={off_mode} W={W} d={d} lazy={lazy}")
+    H, T, seed = (1, 7, 424242) if algo == "adagrad" else (3, 10, 434343)
+    eta, eps, b0 = (0.3, 1.0, 0.0) if algo == "adagrad" else (0.05, 1.0, 1.0)       # eta a < 2 for plain SGD
+    rng = np.random.default_rng(19)
+    a = rng.uniform(0.1, 10, d).astype(np.float32)
+    xs = rng.standard_normal(d).astype(np.float32)
+    off = (0.1 * rng.standard_normal((W, d))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    gm = {"quad": oracle.GEN_QUADRATIC, "noise": oracle.GEN_NOISE}[mode]
+    om = {"none": oracle.OFF_NONE, "array": oracle.OFF_ARRAY, "philox": oracle.OFF_PHILOX}[off_mode]
+    o = Oracle(d, W, H, eta, eps, b0); o.init_state(x0)
+    o.set_generator(gm, seed, a, xs, off if off_mode == "array" else None, om, 0.1, 0.1)
+    g = B.LocalAdaAlter(d, W, H, eta, eps, b0=b0)
+    g.set_algorithm(B.ALGO_DIST_ADAGRAD if algo == "adagrad" else B.ALGO_LOCAL_SGD)
+    g.set_lazy_replicas(lazy)
+    g.init_state(dev(x0))
+    g.set_generator(gm, seed, dev(a), dev(xs) if mode == "quad" else None, dev(off) if off_mode == "array" else None,
+                    om, 0.1, 0.1)
+    single = algo == "adagrad" and lazy          # Algorithm 1's one iterate lives in row 0 of x and in snap
+    sc = parity.Scale(o)
+    S2 = np.zeros(d)                             # largest squared magnitude of the gradient's terms so far, per column
+    for t in range(1, T + 1):
+        x_before = o.x
+        G_ref = o.gradient(t)
+        G_gpu = host(g.generate_gradient())
+        scale = _gen_scale(a, x_before, xs, 0.1, 0.1) if mode == "quad" else np.abs(a)[None, :] * 5
+        err = np.max(np.abs(G_gpu - G_ref) / scale)
+        assert err <= 1e-6, f"gradient at t={t}: {err:.2e}"
+        np.maximum(S2, np.max(scale * np.ones((W, 1)), axis=0) ** 2, out=S2)
+        (o.adagrad_step_dense if algo == "adagrad" else o.localsgd_step_dense)(G_ref)
+        g.step_gen(); sc.update(o)
+        assert g.counters()[0] == o.t
+        gx = host(g.x)
+        if single:
+            gx = np.broadcast_to(gx[:1], gx.shape)
+        ex = parity.rel_err(gx, o.x, 1.0, sc.s)
+        assert ex <= 1e-5, f"{algo} t={t}: x {ex:.2e}"
+        if algo == "adagrad":
+            # B2 starts at 0 here (Algorithm 1), so its error is relative to the squared magnitude of the gradient's
+            # terms: d(g^2) = 2 g dg with dg bounded by 1e-6 of that magnitude, whatever cancels inside g
+            es = parity.rel_err(host(g.snap), o.snap, 1e-3, S2)
+            assert es <= 1e-5, f"adagrad t={t}: B2 {es:.2e}"
+    if single:
+        g.materialize()
+        torch.cuda.synchronize()
+        assert all(torch.equal(g.x[0], g.x[w]) and torch.equal(g.acc[w], g.snap) for w in range(W))
+    if algo == "adagrad":
+        assert parity.rel_err(host(g.acc), o.acc, 1e-3, S2[None, :]) <= 1e-5
+
+
 # ------------------------------------------------------------------------------------------ benchmark configurations
 def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
     """GPU instance at the full size of workload c and an oracle that follows a sample of its columns.
@@ -958,6 +1077,7 @@ def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
     o = Oracle(len(cols), c.W, c.H, c.eta, c.eps)
     o.set_columns(cols); o.init_state()
     o.set_generator(oracle.GEN_QUADRATIC, c.seed, a[cols], xs[cols], None, om, c.noise_scale, c.off_scale)
+    o.sample_a, o.sample_xs = a[cols], xs[cols]
     if bench_layout:
         import torch
         rd = max(wl.SPREAD_ROW_DISTANCE, c.d)
@@ -980,13 +1100,25 @@ def _sampled(t, cols):
     return host(t.index_select(t.dim() - 1, idx))
 
 
+def _first_step_with_bound(c, cols, o, g, what):
+    """Iteration 1 of a quadratic workload on both sides (same initial state), checked against the one-step bound
+    the arithmetic gives (parity.assert_one_step_generated) on the sampled columns."""
+    x_before, G_ref = o.x, o.gradient(1)
+    S = _gen_scale(o.sample_a, x_before, o.sample_xs, c.off_scale, c.noise_scale)
+    den = np.sqrt(o.snap + c.eps * c.eps)[None, :]
+    o.step_gen(); g.step_gen()
+    r = parity.assert_one_step_generated(_sampled(g.x, cols), _sampled(g.acc, cols), x_before, o, G_ref, S, c.eta, den, what)
+    say(f"   {what}: one generated step is {r[0]:.2f} (x), {r[1]:.2f} (acc) of the 1e-6 bound")
+
+
 def test_config1_full_run_on_sampled_columns(B):
     """d=2^20, W=4, H=4, T=64 (the small configuration), full length, oracle on 4096 sampled columns."""
     c = wl.WORKLOADS["c1"]
     cols, o, g = _quadratic_setup(B, c, 1024)
-    for t in range(1, c.T + 1):
+    _first_step_with_bound(c, cols, o, g, "c1 t=1")
+    for t in range(2, c.T + 1):
         o.step_gen(); g.step_gen()
-        if t in (1, c.H, c.T):
+        if t in (c.H, c.T):
             e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
                                     floor_x=1.0, what=f"c1 t={t}")
             say(f"   c1 t={t} rel err", e)
@@ -1000,7 +1132,8 @@ def test_config2_full_length_on_sampled_columns(B):
     """d=25M, W=8, H=8, curvature log-uniform on [1e-3, 1e2], all T = 256 iterations; the oracle follows 4096 columns."""
     c = wl.WORKLOADS["c2"]
     cols, o, g = _quadratic_setup(B, c, 1024)
-    for t in range(1, c.T + 1):
+    _first_step_with_bound(c, cols, o, g, "c2 t=1")
+    for t in range(2, c.T + 1):
         o.step_gen(); g.step_gen()
         if t in (2 * c.H + 1, c.T):
             e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
@@ -1013,11 +1146,9 @@ def test_config5_headline_size_two_periods_on_sampled_columns(B):
     import torch
     c = wl.WORKLOADS["c5"]
     cols, o, g = _quadratic_setup(B, c, 512, bench_layout=True)
-    for t in range(1, 2 * c.H + 1):
+    _first_step_with_bound(c, cols, o, g, "c5 t=1")
+    for t in range(2, 2 * c.H + 1):
         o.step_gen(); g.step_gen()
-        if t == 1:
-            parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
-                                floor_x=1.0, what="c5 t=1")
     g.materialize()                                   # the last iteration averaged: expand the collapsed state
     e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, 1e-5,
                             floor_x=1.0, what="c5")
@@ -1086,46 +1217,80 @@ def test_config3_explicit_gradient_pool(B, H, T):
     torch.cuda.empty_cache()
 
 
-def test_config4_embedding_table_sampled_rows(B):
-    """800,000 x 512 table, W=8, k=8192 Zipf(1.1) rows per worker and step; oracle follows a sample of rows."""
+def test_config4_embedding_table_and_dense_blocks_full_length(B):
+    """800,000 x 512 table, W=8, k=8192 Zipf(1.1) rows per worker and step, plus the 4 dense 2048 x 8192 blocks with
+    the noise generator, for all T = 256 iterations of the configuration (16 periods of H = 16), as the benchmark
+    runs it: row-sparse step + averaging of the touched rows on the table's handle, fused generator step with lazy
+    replicas on the dense blocks' handle.  The oracle follows a sample of table rows (the 8 most frequent, 24 drawn
+    from the first period's rows, 16 from the tail of the vocabulary) and a sample of the blocks' columns.  Row sets
+    are drawn afresh for every iteration; the row values are drawn for the 16 iterations of the first period and
+    used again in the later ones (drawing 33 M normals per iteration on the host would take minutes)."""
     import torch
     c = wl.WORKLOADS["c4"]
-    H, T = c.H, 2 * c.H + 1                 # two periods of the configuration's H = 16 and one step more
+    H, T = c.H, c.T
     zipf = wl.ZipfRows(c.rows, c.zipf_s)
     g = B.LocalAdaAlter(c.d, c.W, H, c.eta, c.eps); g.init_state()
-    all_idx = [wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, with_vals=False)[0] for t in range(1, T + 1)]
-    steps = (wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, c.val_sigma) for t in range(1, T + 1))
-    # sample: the 8 hottest rows, 24 rows drawn from those touched, 8 rows never touched
-    touched = np.unique(np.concatenate([i.ravel() for i in all_idx]))
+    first_period = [wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, c.val_sigma) for t in range(1, H + 1)]
+    vals_dev = [dev(v) for _, v in first_period]
     rng = np.random.default_rng(4)
-    never = np.setdiff1d(np.arange(c.rows), touched)[:8]
-    sample = np.unique(np.concatenate([np.arange(8), rng.choice(touched, 24, replace=False), never]))
+    seen = np.unique(np.concatenate([i.ravel() for i, _ in first_period]))
+    tail = np.arange(c.rows - 1, c.rows - 1 - 16 * 997, -997)                    # 16 rows from the rare end
+    sample = np.unique(np.concatenate([np.arange(8), rng.choice(seen, 24, replace=False), tail]))
     remap = -np.ones(c.rows, dtype=np.int64); remap[sample] = np.arange(sample.size)
     o = Oracle(sample.size * c.row_len, c.W, H, c.eta, c.eps); o.init_state()
-    union = set()
+    # the dense blocks: one handle over their concatenation, as in the benchmark
+    dd = sum(r * q for r, q in c.dense_blocks)
+    sig = wl.sigma(dd, c.seed)
+    dcols = wl.column_sample(dd, 256, seed=3)
+    gd = B.LocalAdaAlter(dd, c.W, H, c.eta, c.eps); gd.set_lazy_replicas(True); gd.init_state()
+    gd.set_generator(B.GEN_NOISE, c.seed, dev(sig))
+    od = Oracle(len(dcols), c.W, H, c.eta, c.eps); od.set_columns(dcols); od.init_state()
+    od.set_generator(oracle.GEN_NOISE, c.seed, sig[dcols])
+    union, ever = set(), set()
     sc = parity.Scale(o)
-    for t, (idx, vals) in enumerate(steps, start=1):
-        assert np.array_equal(idx, all_idx[t - 1])
-        g.local_step_sparse(dev(idx), dev(vals), c.row_len)
-        # the oracle sees each worker's sampled rows only (padded per worker to a common k with zero rows is not
-        # needed: a dense step on the scattered gradient is the definition)
+    cols = (sample[:, None] * c.row_len + np.arange(c.row_len)[None, :]).reshape(-1)
+    for t in range(1, T + 1):
+        if t <= H:
+            idx, vals = first_period[t - 1]
+        else:
+            idx = wl.sparse_step(zipf, c.W, c.k, c.row_len, c.seed, t, with_vals=False)[0]
+            vals = first_period[(t - 1) % H][1]
+        g.local_step_sparse(dev(idx), vals_dev[(t - 1) % H], c.row_len)
+        # the oracle takes the dense step on the scattered gradient of the sampled rows: that is the definition
         G = np.zeros((c.W, sample.size, c.row_len))
         for w in range(c.W):
             m = remap[idx[w]]
             G[w, m[m >= 0]] = vals[w][m >= 0]
         o.local_step_dense(G.reshape(c.W, -1)); sc.update(o)
-        union |= set(idx.ravel().tolist())
+        rows_t = set(idx.ravel().tolist())
+        union |= rows_t; ever |= rows_t
+        gd.step_gen(); od.step_gen()
         if t == 1:
             assert np.array_equal(g.dirty_rows(), np.array(sorted(union), dtype=np.int32))
         if t % H == 0:
-            assert np.array_equal(g.dirty_rows(), np.array(sorted(union), dtype=np.int32))
+            if t in (H, T):
+                assert np.array_equal(g.dirty_rows(), np.array(sorted(union), dtype=np.int32)), f"dirty rows at t={t}"
             g.sync(); o.sync(); union = set()
-    cols = (sample[:, None] * c.row_len + np.arange(c.row_len)[None, :]).reshape(-1)
-    parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o, parity.FULL_RUN,
-                        what="c4", scale=sc)
-    assert g.counters(with_bad=True)[2] == 0
-    # rows nobody touched keep their initial state on every worker
+        if t in (1, H, T // 2, T):
+            torch.cuda.synchronize()
+            e = parity.assert_state(_sampled(g.x, cols), _sampled(g.acc, cols), _sampled(g.snap, cols), o,
+                                    parity.FULL_RUN, what=f"c4 table t={t}", scale=sc)
+            if t % H == 0:                # the blocks were just averaged: row 0 of x and snap hold the state
+                ex = parity.rel_err(_sampled(gd.x[:1], dcols), od.x[:1], 1.0)
+                es = parity.rel_err(_sampled(gd.snap, dcols), od.snap, 1e-3)
+            else:
+                ex = parity.rel_err(_sampled(gd.x, dcols), od.x, 1.0)
+                es = parity.rel_err(_sampled(gd.acc, dcols), od.acc, 1e-3)
+            say(f"   c4 t={t}: table rel err {e}, dense blocks x {ex:.2e} B2 {es:.2e}")
+            assert ex <= 1e-5 and es <= 1e-5, f"c4 dense blocks at t={t}: x {ex:.2e} B2 {es:.2e}"
+    assert g.counters(with_bad=True) == (T, 0, 0) and gd.counters() == (T, 0)
+    gd.materialize()
+    parity.assert_state(_sampled(gd.x, dcols), _sampled(gd.acc, dcols), _sampled(gd.snap, dcols), od, 1e-5,
+                        floor_x=1.0, what="c4 dense blocks")
+    # sampled rows nobody touched keep their initial state on every worker, bit for bit
+    never = np.array([r for r in sample if r not in ever], dtype=np.int64)
+    assert never.size > 0
     nv = (never[:, None] * c.row_len + np.arange(c.row_len)[None, :]).reshape(-1)
-    assert np.all(_sampled(g.x, nv) == 0.0) and np.all(_sampled(g.acc, nv) == 1.0)
-    del g
+    assert np.all(_sampled(g.x, nv) == 0.0) and np.all(_sampled(g.acc, nv) == 1.0) and np.all(_sampled(g.snap, nv) == 1.0)
+    del g, gd
     torch.cuda.empty_cache()
