@@ -57,6 +57,11 @@ def parse():
     p.add_argument("--calibrate-copy", type=int, default=0,
                    help="after the run, launch the plain copy kernel this many times over one row of d floats "
                         "(a known volume for scaling profiler byte counters)")
+    p.add_argument("--reps", type=int, default=5,
+                   help="repetitions of the timed region of --steps iterations; value is the median over them")
+    p.add_argument("--no-packed-compare", action="store_true",
+                   help="skip the short run in the packed layout that is reported next to the spread one (c5 default run)")
+    p.add_argument("--cpu-reps", type=int, default=3, help="repetitions of the one-core CPU baseline (median reported)")
     p.add_argument("--cpu-sample-d", type=int, default=524_288)
     p.add_argument("--cpu-procs", type=int, default=min(16, os.cpu_count() or 1),
                    help="processes of the all-cores CPU baseline (1 switches it off)")
@@ -66,15 +71,17 @@ def parse():
 
 
 def traffic_from_profile(kernel_tag: str):
-    """Last profiled HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated), if recorded."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{kernel_tag}.txt")
+    """HBM bytes per launch of the dominant kernel as last profiled (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a
+    copy of known size) and the committed file it is read from; (None, None) if there is none.  A stored figure:
+    counters cannot be collected from inside this run."""
+    rel = os.path.join("profiles", f"hbm_traffic_{kernel_tag}.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("bytes_per_launch:"):
-                return float(line.split(":")[1])
+                return float(line.split(":")[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def _oracle_period(c, lo, n, offsets):
@@ -97,15 +104,18 @@ def _oracle_period(c, lo, n, offsets):
     return time.perf_counter() - t0
 
 
-def cpu_baseline(c, sample_d, offsets, procs):
-    """The oracle as it stands (single thread, fp64) on a column slice of the same workload, one sync period; then
-    the same oracle as `procs` independent single-threaded processes on disjoint column slices (columns are
-    independent, so this is the same computation)."""
+def cpu_baseline(c, sample_d, offsets, procs, reps):
+    """The oracle as it stands (single thread, fp64) on a column slice of the same workload, one sync period, median of
+    `reps` runs; then the same oracle once as `procs` independent single-threaded processes on disjoint column slices
+    (columns are independent, so this is the same computation)."""
+    import statistics
     import subprocess
-    dt = _oracle_period(c, 0, sample_d, offsets)
+    times = [_oracle_period(c, 0, sample_d, offsets) for _ in range(max(reps, 1))]
+    dt = statistics.median(times)
     out = {"value": c.W * sample_d * c.H / dt, "unit": "element-updates/s", "cores": 1, "kind": "oracle",
+           "columns": sample_d, "repetitions": len(times), "seconds": [round(t, 2) for t in times],
            "sample": f"first {sample_d} columns of {c.name}, W={c.W}, one sync period of H={c.H} steps, fp64, "
-                     f"{dt:.1f} s"}
+                     f"median of {len(times)} runs: {dt:.1f} s"}
     if procs > 1:
         kids = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--workload", c.name, "--offsets", offsets,
                                   "--cpu-slice", str(i * sample_d), str(sample_d)], stdout=subprocess.PIPE, text=True)
@@ -113,8 +123,8 @@ def cpu_baseline(c, sample_d, offsets, procs):
         times = [float(k.communicate()[0].strip().splitlines()[-1]) for k in kids]
         if all(k.returncode == 0 for k in kids):
             out["all_cores"] = {"value": procs * c.W * sample_d * c.H / max(times), "unit": "element-updates/s",
-                                "cores": procs, "kind": "oracle",
-                                "sample": f"{procs} processes x {sample_d} disjoint columns, slowest {max(times):.1f} s"}
+                                "cores": procs, "kind": "oracle", "columns": procs * sample_d,
+                                "sample": f"{procs} processes x {sample_d} disjoint columns, one run, slowest {max(times):.1f} s"}
     return out
 
 
@@ -255,40 +265,75 @@ def main():
     if not args.no_lazy_replicas and c.kind == "embedding":
         gd.set_lazy_replicas(True)       # the dense blocks; the table's sparse sync never collapses
 
-    # warm-up (untimed), then realign to a period boundary so the timed region holds K/H syncs
+    handles = [g] + ([gd] if c.kind == "embedding" else [])
+
+    def moved_bytes():
+        m = [h.bytes_moved(literal=True) for h in handles]
+        return sum(v[0] for v in m), sum(v[1] for v in m)
+
+    # Warm-up (untimed), then on to the iteration right after an averaging one.  From there K timed iterations hold
+    # floor(K / H) averaging iterations and as many that read the collapsed state, never more: a K that is not a whole
+    # number of periods is not flattered by the cheaper iterations.  (Replayed periods start on a period boundary.)
+    phase = 0 if args.graph else 1 % H
     t = 0
+
+    def align():
+        nonlocal t
+        while t == 0 or t % H != phase:
+            t += 1
+            do_step(t)
+
     for _ in range(Wm):
         t += 1
         do_step(t)
-    while t % H:
-        t += 1
-        do_step(t)
-    torch.cuda.synchronize()
-
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
-    if c.kind == "embedding":
-        mid.update({t + i + 1: torch.cuda.Event(enable_timing=True) for i in range(K)})
-    t_first = t + 1
+    align()
     if args.graph:
         K -= K % H
         g.run_periods_gen(3)                 # the first period of each kind runs as plain launches, the third records
+        t += 3 * H
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev[0].record()
-    if args.graph:
-        g.run_periods_gen(K // H)
-        ev[K].record()
-    else:
-        for i in range(K):
-            t += 1
-            do_step(t)
-            ev[i + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
 
-    if args.graph:                           # no events inside a replayed period: the average over all iterations
-        assert g.replay_count() >= K // H, "the periods were not replayed from a graph"
-        per_step_ms = [ev[0].elapsed_time(ev[K]) / K] * K
+    reps = max(args.reps, 1)
+    per_step_ms, kinds, walls = [], [], []   # over all repetitions; kind: "plain", "sync" (averages), "post" (reads the collapsed state)
+    bytes_timed = [0, 0]                     # moved and literal bytes of the timed iterations (not of the realignment between repetitions)
+    for _ in range(reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        if c.kind == "embedding":
+            mid.clear()
+            mid.update({t + i + 1: torch.cuda.Event(enable_timing=True) for i in range(K)})
+        t_first = t + 1
+        bytes_before = moved_bytes()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev[0].record()
+        if args.graph:
+            g.run_periods_gen(K // H)
+            t += K
+            ev[K].record()
+        else:
+            for i in range(K):
+                t += 1
+                do_step(t)
+                ev[i + 1].record()
+        torch.cuda.synchronize()
+        walls.append(time.perf_counter() - t0)
+        bytes_after = moved_bytes()
+        bytes_timed = [bytes_timed[k] + bytes_after[k] - bytes_before[k] for k in (0, 1)]
+        if args.graph:                       # no events inside a replayed period: the average over all iterations
+            ms = [ev[0].elapsed_time(ev[K]) / K] * K
+        elif c.kind == "embedding":          # the roofline line is the row-sparse step alone
+            ms = [ev[i].elapsed_time(mid[t_first + i]) for i in range(K)]
+        else:
+            ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
+        per_step_ms += ms
+        # iteration tt averages when tt % H == 0 and, with lazy replicas, reads a collapsed state when the one before it averaged
+        for i in range(K):
+            tt = t_first + i
+            kinds.append("sync" if tt % H == 0 else "post" if lazy and tt > 1 and (tt - 1) % H == 0 else "plain")
+        align()
+    n_timed = reps * K
+    if args.graph:
+        assert g.replay_count() >= reps * (K // H), "the periods were not replayed from a graph"
         graph_inputs = step_bytes // d - (16 * W + 4)
         lazy_on = not args.no_lazy_replicas
         if H == 1:
@@ -299,45 +344,51 @@ def main():
         else:
             period_cols = (H - 1) * (16 * W + 4 + graph_inputs) + (16 * W + 8 + graph_inputs)
         graph_step_bytes = period_cols * d // H
-    else:
-        per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
-    if c.kind == "embedding":                 # the roofline line is the row-sparse step alone
-        per_step_ms = [ev[i].elapsed_time(mid[t_first + i]) for i in range(K)]
-    # the dominant kernel is the plain step: not the averaging one ((i+1) % H == 0) and, with lazy replicas, not the
-    # one right after it (i % H == 0), which reads the collapsed state
+
+    # the dominant kernel is the plain step: neither the averaging one nor, with lazy replicas, the one right after it
     kernel_name = kernel_tag.rsplit("_", 1)[0]
-    # timed iteration i is iteration t_first + i of the run; the warm-up ends on a period boundary, so iteration i
-    # averages when (i + 1) % H == 0, and reads a collapsed state when the iteration before it averaged
-    after_sync = [lazy and i % H == 0 and t_first + i > 1 for i in range(K)]
-    plain = [per_step_ms[i] for i in range(K) if (i + 1) % H != 0 and not after_sync[i]]
+    by_kind = {k: [m for m, kk in zip(per_step_ms, kinds) if kk == k] for k in ("plain", "sync", "post")}
+    plain = by_kind["plain"]
     if not plain and c.kind != "embedding":
         # No plain step among the timed iterations (H = 1, H = 2 with lazy replicas, or very few iterations): the
         # dominant kernel is the averaging step if there is one, else the step that reads the collapsed state.
         inputs = step_bytes // d - (16 * W + 4)
-        sync_idx = [i for i in range(K) if (i + 1) % H == 0]
-        if sync_idx:            # reads the state (collapsed if the iteration before averaged too), writes the means
-            state_in = 8 if after_sync[sync_idx[-1]] else 8 * W + 4
+        if by_kind["sync"]:     # reads the state (collapsed if the iteration before averaged too), writes the means
+            state_in = 8 if (lazy and H == 1) else 8 * W + 4
             state_out = 8 if lazy else 8 * W + 4
             step_bytes = (state_in + inputs + state_out) * d
             kernel_tag += "_sync"
             kernel_name += " (averaging step)"
-            plain = [per_step_ms[i] for i in sync_idx if after_sync[i] == after_sync[sync_idx[-1]]]
+            plain = by_kind["sync"]
         else:                   # reads row 0 of x, snap and the inputs, writes every worker's rows
             step_bytes = (8 + inputs + 8 * W) * d
             kernel_tag += "_after_sync"
             kernel_name += " (step after an averaging)"
-            plain = per_step_ms
+            plain = by_kind["post"]
     if not plain:
         plain = per_step_ms
     if args.graph:
         plain, step_bytes = per_step_ms, graph_step_bytes
         kernel_tag += "_graph"
         kernel_name += " (average over the iterations of a replayed period)"
-    post_sync = [per_step_ms[i] for i in range(K) if after_sync[i] and (i + 1) % H != 0]
-    sync_it = [per_step_ms[i] for i in range(K) if (i + 1) % H == 0]
+    import statistics
     kern_ms = sum(plain) / len(plain)
     achieved = step_bytes / (kern_ms * 1e-3) / 1e9
-    value = updates_per_step * K / wall
+    values = [updates_per_step * K / w for w in walls]
+    value = statistics.median(values)
+    mean_of = lambda v: (sum(v) / len(v)) if v else None
+    ms_sync, ms_post = mean_of(by_kind["sync"]), mean_of(by_kind["post"])
+    # one whole period in the steady state, from the per-kind iteration times: independent of how many iterations of
+    # each kind the timed region happened to hold
+    steady_ms = steady_value = None
+    if not args.graph and c.kind != "embedding":
+        n_post = 1 if (lazy and H >= 2) else 0
+        parts = [(H - 1 - n_post, mean_of(by_kind["plain"])), (1, ms_sync), (n_post, ms_post)]
+        if all(n == 0 or m is not None for n, m in parts):
+            steady_ms = sum(n * m for n, m in parts if n) / H
+            steady_value = updates_per_step / (steady_ms * 1e-3)
+    moved = bytes_timed[0] / (updates_per_step * n_timed)
+    literal = bytes_timed[1] / (updates_per_step * n_timed)
 
     g.materialize()
     assert bool(torch.isfinite(g.x[W - 1, :4096]).all()), "non-finite parameters after the run"
@@ -357,27 +408,68 @@ def main():
         torch.cuda.synchronize()
         copy_gbs = 20 * 8 * d / (c0.elapsed_time(c1) * 1e-3) / 1e9
 
+    # The same workload in ordinary packed tensors, a short run next to the spread one (the spread layout is this
+    # benchmark's choice of placement; a caller with plain allocations gets this figure).
+    packed = None
+    if (c.kind == "quadratic" and spread and layouts and layouts[0].startswith("spread") and not args.graph
+            and not args.no_packed_compare and not args.unfused_sync and args.offsets != "array"):
+        pa, pxs = a.clone(), xs.clone()
+        gp = B.LocalAdaAlter(d, W, H, c.eta, c.eps)
+        gp.init_state()
+        gp.set_generator(B.GEN_QUADRATIC, c.seed, pa, pxs, None, om, c.noise_scale, c.off_scale)
+        if args.tile is not None:
+            gp.set_tile(args.tile)
+        gp.set_lazy_replicas(lazy)
+        Kp = max(H, min(K, 4 * H))
+        for _ in range(H + 1):
+            gp.step_gen()
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(Kp + 1)]
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        pe[0].record()
+        for i in range(Kp):
+            gp.step_gen()
+            pe[i + 1].record()
+        torch.cuda.synchronize()
+        pwall = time.perf_counter() - p0
+        pk = [pe[i].elapsed_time(pe[i + 1]) for i in range(Kp)
+              if (H + 2 + i) % H != 0 and not (lazy and (H + 1 + i) % H == 0)]
+        packed = {"value": updates_per_step * Kp / pwall, "steps": Kp,
+                  "kernel_ms": (sum(pk) / len(pk)) if pk else None,
+                  "frac": (step_bytes / (sum(pk) / len(pk) * 1e-3) / 1e9 / HBM_PEAK_GBS) if pk else None}
+        del gp, pa, pxs
+
+    traffic, traffic_source = traffic_from_profile(kernel_tag)
+    frac = achieved / HBM_PEAK_GBS
     out = {
         "metric": "element-updates/sec and achieved HBM GB/s (% of peak), step+sync, 1 GPU",
         "value": value, "unit": "element-updates/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": wall * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": updates_per_step / value * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
                                f"lazy_replicas={'on' if lazy else 'off'} layout={'+'.join(layouts)}"
                                f"{' periods replayed from a HIP graph' if args.graph else ''}",
-                   "syncs_in_timed_region": len(sync_it),
-                   "ms_sync_iteration": (sum(sync_it) / len(sync_it)) if sync_it else None,
-                   "ms_post_sync_iteration": (sum(post_sync) / len(post_sync)) if post_sync else None,
-                   "method_bytes_per_element_update": 16 + 4 / W + (16 * W + 4) / (W * H)},
+                   "repetitions": reps, "value_is": f"median over {reps} repetitions of {K} timed iterations",
+                   "values": values,
+                   "timed_iterations_by_kind": {k: len(v) for k, v in by_kind.items()},
+                   "ms_sync_iteration": ms_sync, "ms_post_sync_iteration": ms_post,
+                   "ms_per_step_steady_state": steady_ms, "value_steady_state": steady_value,
+                   "bytes_per_element_update_moved": moved, "bytes_per_element_update_literal": literal,
+                   "packed_layout": packed,
+                   "parity_bar": "1e-5 relative to max(|ref|, largest |x| on the trajectory, floor); floor 1 for x on "
+                                 "generated gradients, 1e-3 otherwise"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(kernel_tag),
-                     "kernel": kernel_name, "kernel_ms": kern_ms,
+                     "frac": frac, "target_frac": 0.80, "meets_target": frac >= 0.80,
+                     "traffic": traffic, "traffic_source": (f"stored: {traffic_source} (rocprofv3 counters of an earlier run "
+                                                            "of this command, not measured in this run)") if traffic_source else None,
+                     "kernel": kernel_name, "kernel_ms": kern_ms, "kernel_ms_min": min(plain),
+                     "kernel_ms_median": statistics.median(plain), "kernel_ms_max": max(plain), "kernel_launches_timed": len(plain),
                      "algorithmic_bytes_per_launch": step_bytes, "copy_kernel_gbs_same_run": copy_gbs},
     }
     if not args.no_cpu_baseline and c.kind == "quadratic":
-        out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets, args.cpu_procs)
+        out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets, args.cpu_procs, args.cpu_reps)
     print(json.dumps(out), flush=True)
 
 
