@@ -42,9 +42,12 @@ def parse():
     p.add_argument("--tile", type=int, default=None,
                    help="laa_set_tile: workers loaded per batch (1, 2, 4, 8), or 0 for one worker per thread block")
     p.add_argument("--pitch", type=int, default=0, help="row pitch of x/acc in elements (0: dense rows of d)")
-    p.add_argument("--layout", default="spread", choices=["spread", "packed"],
-                   help="spread: all [W][d] rows and [d] vectors up to 10 GB apart over the HBM address range "
+    p.add_argument("--layout", default="tuned", choices=["tuned", "spread", "packed"],
+                   help="tuned: the arrays' places inside a pool of most of the free memory are chosen by timing the "
+                        "step on candidate placements (placement.tune), the rest of the pool is released; "
+                        "spread: all [W][d] rows and [d] vectors up to 10 GB apart over the HBM address range "
                         "(binding.spread_arrays); packed: ordinary dense tensors")
+    p.add_argument("--placements", type=int, default=48, help="random candidate placements of the tuned layout")
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -163,9 +166,32 @@ def main():
     pitch = args.pitch or None
     spread = args.layout != "packed"
     keep, layouts = [], []
+    tuning = {}
 
-    def alloc(dd, n_mat, n_vec):
-        """n_mat arrays [W][dd] and n_vec arrays [dd]: spread over the address range, else ordinary tensors."""
+    def alloc(dd, n_mat, n_vec, measure=None):
+        """n_mat arrays [W][dd] and n_vec arrays [dd]: at measured places inside a pool (when a measure is given),
+        spread over the address range, else ordinary tensors."""
+        if args.layout == "tuned" and measure is not None:
+            from paper_1911_09030_amd import placement
+            pool = None
+            try:
+                free = torch.cuda.mem_get_info(dev)[0]
+                t_tune = time.perf_counter()
+                pool = B.Pool(int(free * 0.9), device=dev)
+                best = placement.tune(pool, dd, W, n_mat, n_vec, measure, n_random=args.placements, seed=c.seed)
+                mats, vecs = placement.views(pool, dd, W, best)
+                pool.trim(best.ranges(dd, W))
+                keep.append(pool)
+                layouts.append(f"tuned(pitch {best.pitch})")
+                tuning.update({"placements_timed": best.tried, "best_ms": best.ms, "median_ms": best.median_ms,
+                               "slowest_ms": best.slowest_ms, "pool_gb": pool.nbytes / 1e9,
+                               "seconds": time.perf_counter() - t_tune,
+                               "matrices_at_gb": [m * 4 / 1e9 for m in best.matrices], "vectors_at_gb": [v * 4 / 1e9 for v in best.vectors]})
+                return mats, vecs, best.pitch
+            except (B.LaaError, RuntimeError, ValueError) as e:
+                print(f"bench.py: tuned layout unavailable for d={dd} ({e}); spread layout instead", file=sys.stderr)
+                if pool is not None:
+                    pool.close()
         if spread:
             try:
                 backing, mats, vecs, rp = B.spread_arrays(dd, W, n_mat, n_vec, args.row_distance or wl.SPREAD_ROW_DISTANCE,
@@ -183,7 +209,11 @@ def main():
 
     if c.kind == "quadratic":
         with_off = args.offsets == "array"
-        mats, (bsnap, a, xs), rp = alloc(d, 3 if with_off else 2, 3)
+        om = {"philox": B.OFF_PHILOX, "array": B.OFF_ARRAY, "none": B.OFF_NONE}[args.offsets]
+
+        from paper_1911_09030_amd import placement
+        measure = placement.quadratic_step_timer(d, W, c.eta, c.eps, c.seed, om, c.noise_scale, c.off_scale, args.tile)
+        mats, (bsnap, a, xs), rp = alloc(d, 3 if with_off else 2, 3, measure)
         g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
         a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
         xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
@@ -193,7 +223,6 @@ def main():
             off = mats[2]
             for w in range(W):      # inputs only: N(0, off_scale^2) drawn on the device, one worker row at a time
                 off[w].normal_(0.0, c.off_scale)
-        om = {"philox": B.OFF_PHILOX, "array": B.OFF_ARRAY, "none": B.OFF_NONE}[args.offsets]
         g.set_generator(B.GEN_QUADRATIC, c.seed, a, xs, off, om, c.noise_scale, c.off_scale)
         step_bytes = (16 * W + 12 + (4 * W if off is not None else 0)) * d
         kernel_tag = f"step_kernel_{c.name}"
@@ -208,7 +237,27 @@ def main():
         updates_per_step = W * d
     elif c.kind == "explicit":
         P = 4
-        mats, (bsnap, sig), rp = alloc(d, 2 + P, 2)
+
+        def measure(mats, vecs, rp):
+            """The explicit-gradient step streaming the pool of gradient tensors, arrays at a candidate placement."""
+            for m in mats[2:]:
+                m.zero_()
+            h = B.LocalAdaAlter(d, W, 1 << 30, c.eta, c.eps, x=mats[0], acc=mats[1], snap=vecs[0], pitch=rp)
+            h.init_state()
+            if args.tile is not None:
+                h.set_tile(args.tile)
+            k = [0]
+
+            def one():
+                k[0] += 1
+                h.step_dense(mats[2 + k[0] % P])
+            one()
+            from paper_1911_09030_amd.placement import event_median_ms
+            ms = event_median_ms(one, n=2 * P + 1)
+            h.close()
+            return ms
+
+        mats, (bsnap, sig), rp = alloc(d, 2 + P, 2, measure)
         g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
         g.init_state()
         sig.copy_(torch.from_numpy(wl.sigma(d, c.seed)))
@@ -287,6 +336,28 @@ def main():
         t += 1
         do_step(t)
     align()
+    # Memory that the layout gave back to the driver (the unused part of the pool, the spacers of the spread layout)
+    # is cleared by the driver in the background for some seconds, which takes a little bandwidth from everything
+    # that runs meanwhile (measured: the step 0.7 % slower for up to 20 s after 240 GB were released).  Keep
+    # stepping, untimed, until whole periods stop getting faster.
+    settle = None
+    if spread and not args.graph and c.kind != "embedding":
+        t_settle, hist = time.perf_counter(), []
+        while time.perf_counter() - t_settle < 45.0:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_it = max(H, (64 // H) * H)
+            e0.record()
+            for _ in range(n_it):
+                t += 1
+                do_step(t)
+            e1.record()
+            torch.cuda.synchronize()
+            hist.append(e0.elapsed_time(e1) / n_it)
+            if len(hist) >= 4 and max(hist[-3:]) < min(hist[-3:]) * 1.0005:      # three windows in a row within 0.05 %
+                break
+        settle = {"seconds": time.perf_counter() - t_settle, "untimed_iterations": len(hist) * n_it,
+                  "ms_per_iteration_first_window": hist[0], "ms_per_iteration_at_end": hist[-1]}
+        align()
     if args.graph:
         K -= K % H
         g.run_periods_gen(3)                 # the first period of each kind runs as plain launches, the third records
@@ -411,7 +482,7 @@ def main():
     # The same workload in ordinary packed tensors, a short run next to the spread one (the spread layout is this
     # benchmark's choice of placement; a caller with plain allocations gets this figure).
     packed = None
-    if (c.kind == "quadratic" and spread and layouts and layouts[0].startswith("spread") and not args.graph
+    if (c.kind == "quadratic" and spread and layouts and not layouts[0].startswith("packed") and not args.graph
             and not args.no_packed_compare and not args.unfused_sync and args.offsets != "array"):
         pa, pxs = a.clone(), xs.clone()
         gp = B.LocalAdaAlter(d, W, H, c.eta, c.eps)
@@ -457,7 +528,7 @@ def main():
                    "ms_sync_iteration": ms_sync, "ms_post_sync_iteration": ms_post,
                    "ms_per_step_steady_state": steady_ms, "value_steady_state": steady_value,
                    "bytes_per_element_update_moved": moved, "bytes_per_element_update_literal": literal,
-                   "packed_layout": packed,
+                   "packed_layout": packed, "layout_tuning": tuning or None, "settling_after_release": settle,
                    "parity_bar": "1e-5 relative to max(|ref|, largest |x| on the trajectory, floor); floor 1 for x on "
                                  "generated gradients, 1e-3 otherwise"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

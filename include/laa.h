@@ -275,6 +275,24 @@ int laa_spread_alloc(int32_t n_arrays, int64_t array_bytes, int64_t distance_byt
                      int64_t *actual_distance_bytes);
 int laa_spread_free(void *base);
 
+/* A pool of device memory for choosing WHERE the state arrays live (optional, like laa_spread_alloc).
+ * laa_pool_create maps `bytes` of device memory, created as separate physical chunks of chunk_bytes (both
+ * rounded up to the mapping granularity), back to back into one address range starting at *base.
+ * Why: on MI355X the rate of a kernel that streams 2W + 3 arrays at once depends on where those arrays sit in
+ * physical memory relative to one another (measured at d = 4e8, W = 8: 0.69 to 0.80 of the HBM peak over
+ * 235 placements inside one 260 GB range), and nothing but a measurement tells a good placement from a bad
+ * one.  A caller takes a pool of most of the free memory, times the step on candidate placements inside it
+ * (arrays are just offsets into the pool), keeps the best and gives the rest back:
+ * laa_pool_trim unmaps and releases every chunk that none of the n_ranges byte ranges [offsets[r],
+ * offsets[r] + lengths[r]) touches; the kept chunks stay where they are, physically and virtually, so the
+ * measured placement is the one that is used; addresses in released chunks fault when touched.
+ * laa_pool_free releases everything.  Both synchronise the device first.
+ * Errors: LAA_EINVAL (sizes, unknown pointer, a range outside the pool or in a released chunk), LAA_EHIP
+ * (out of memory or address space). */
+int laa_pool_create(int64_t bytes, int64_t chunk_bytes, void **base, int64_t *actual_bytes, int64_t *actual_chunk_bytes);
+int laa_pool_trim(void *base, int32_t n_ranges, const int64_t *offsets, const int64_t *lengths);
+int laa_pool_free(void *base);
+
 /* Test hook: four raw Philox4x32-10 words for one counter/key, computed on the
  * device, copied to out (HOST, 4 words). */
 int laa_debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t *out);

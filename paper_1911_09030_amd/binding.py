@@ -12,7 +12,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblaa.so")
+# LAA_LIB names another build of the same library (for comparing builds); the default is the in-tree one.
+LIB_PATH = os.environ.get("LAA_LIB") or os.path.join(_HERE, "liblaa.so")
 
 OK, EINVAL, ENOTATTACHED, ESYNCDUE, EALIGN, EMODE, EHIP, ENODEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 GEN_QUADRATIC, GEN_NOISE = 1, 2
@@ -24,7 +25,7 @@ EXPORTS = [
     "laa_set_tile", "laa_set_lazy_replicas", "laa_set_sparse_coalesce", "laa_materialize", "laa_attach", "laa_attach_pitched", "laa_init_state", "laa_local_step_dense", "laa_set_generator",
     "laa_local_step_gen", "laa_run_periods_gen", "laa_get_replay_count", "laa_generate_gradient", "laa_local_step_sparse", "laa_sync", "laa_sync_static", "laa_step_dense",
     "laa_step_gen", "laa_step_sparse", "laa_get_counters", "laa_set_counters", "laa_set_shard", "laa_get_dirty_rows", "laa_diagnostics", "laa_bytes_moved",
-    "laa_spread_alloc", "laa_spread_free", "laa_debug_philox", "laa_debug_copy",
+    "laa_spread_alloc", "laa_spread_free", "laa_pool_create", "laa_pool_trim", "laa_pool_free", "laa_debug_philox", "laa_debug_copy",
 ]
 
 _lib = None
@@ -81,6 +82,9 @@ def lib():
         "laa_bytes_moved": [vp, C.POINTER(u64), C.POINTER(u64)],
         "laa_spread_alloc": [i32, i64, i64, C.POINTER(vp), C.POINTER(i64)],
         "laa_spread_free": [vp],
+        "laa_pool_create": [i64, i64, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64)],
+        "laa_pool_trim": [vp, i32, C.POINTER(i64), C.POINTER(i64)],
+        "laa_pool_free": [vp],
         "laa_debug_philox": [vp, vp, vp],
         "laa_debug_copy": [vp, vp, i64, vp],
     }
@@ -125,6 +129,48 @@ class SpreadAllocation:
         _check(lib().laa_spread_alloc(int(n_arrays), int(array_bytes), int(distance_bytes), C.byref(base), C.byref(dist)))
         self.base, self.distance_bytes, self.n_arrays = base.value, dist.value, int(n_arrays)
         self._base_arg = C.c_void_p(base.value)
+
+    def close(self):
+        if getattr(self, "base", None):
+            self._free(self._base_arg)
+            self.base = None
+
+    __del__ = close
+
+
+class Pool:
+    """Device memory from laa_pool_create: one address range backed by separately created chunks, so that the part a
+    caller ends up using can be kept and the rest released (trim).  Tensors are views at element offsets."""
+
+    def __init__(self, nbytes, chunk_bytes=1 << 30, device="cuda:0"):
+        base, total, chunk = C.c_void_p(), C.c_int64(), C.c_int64()
+        self._free = lib().laa_pool_free
+        self.device = device
+        _check(lib().laa_pool_create(int(nbytes), int(chunk_bytes), C.byref(base), C.byref(total), C.byref(chunk)))
+        self.base, self.nbytes, self.chunk_bytes = base.value, total.value, chunk.value
+        self._base_arg = C.c_void_p(base.value)
+
+    def tensor(self, offset, shape, strides=None):
+        """float32 view: `offset` and `strides` in elements."""
+        import torch
+        shape = tuple(int(v) for v in shape)
+        if strides is None:
+            strides, acc = [], 1
+            for n in reversed(shape):
+                strides.insert(0, acc)
+                acc *= n
+        last = int(offset) + sum((n - 1) * int(st) for n, st in zip(shape, strides))
+        if offset < 0 or (last + 1) * 4 > self.nbytes:
+            raise ValueError("view outside the pool")
+        return torch.as_tensor(_DeviceArray(self.base + 4 * int(offset), shape, [4 * int(st) for st in strides], self),
+                               device=self.device)
+
+    def trim(self, ranges):
+        """Keep only the chunks touched by the (offset, length) element ranges; the rest is released."""
+        n = len(ranges)
+        offs = (C.c_int64 * n)(*[4 * int(o) for o, _ in ranges])
+        lens = (C.c_int64 * n)(*[4 * int(l) for _, l in ranges])
+        _check(lib().laa_pool_trim(self._base_arg, n, offs, lens))
 
     def close(self):
         if getattr(self, "base", None):

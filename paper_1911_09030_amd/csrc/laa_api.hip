@@ -937,6 +937,121 @@ int laa_spread_free(void *base)
     return e == hipSuccess ? LAA_OK : hip_fail(e, "hipDeviceSynchronize before freeing a spread allocation");
 }
 
+// ---- chunked pool ------------------------------------------------------------------------------------------
+namespace {
+struct Pool {
+    size_t chunk = 0;
+    std::vector<hipMemGenericAllocationHandle_t> handles;   // one per chunk; 0 once released
+    std::vector<bool> mapped;
+    size_t reserved = 0;                                    // bytes of address range
+};
+std::map<void *, Pool> g_pools;                             // guarded by g_spread_mutex
+
+void pool_release(void *base, Pool &pl)
+{
+    for (size_t i = 0; i < pl.handles.size(); ++i) {
+        if (pl.mapped[i]) (void)hipMemUnmap(static_cast<char *>(base) + i * pl.chunk, pl.chunk);
+        if (pl.handles[i]) (void)hipMemRelease(pl.handles[i]);
+    }
+    if (pl.reserved) (void)hipMemAddressFree(base, pl.reserved);
+}
+}  // namespace
+
+int laa_pool_create(int64_t bytes, int64_t chunk_bytes, void **base, int64_t *actual_bytes, int64_t *actual_chunk_bytes)
+{
+    if (!base) return fail(LAA_EINVAL, "null base");
+    *base = nullptr;
+    if (bytes <= 0 || chunk_bytes <= 0) return fail(LAA_EINVAL, "need bytes > 0 and chunk_bytes > 0");
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(LAA_ENODEVICE, "no HIP device available");
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = dev;
+    size_t gran = 0;
+    if ((e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityRecommended)) != hipSuccess)
+        return hip_fail(e, "hipMemGetAllocationGranularity");
+    if (gran < (size_t(2) << 20)) gran = size_t(2) << 20;
+    Pool pl;
+    pl.chunk = ((size_t)chunk_bytes + gran - 1) / gran * gran;
+    const size_t n = ((size_t)bytes + pl.chunk - 1) / pl.chunk;
+    if (n > 65536) return fail(LAA_EINVAL, "more than 65536 chunks: use larger chunks");
+    void *va = nullptr;
+    if ((e = hipMemAddressReserve(&va, n * pl.chunk, 0, nullptr, 0)) != hipSuccess)
+        return hip_fail(e, "hipMemAddressReserve for a pool");
+    pl.reserved = n * pl.chunk;
+    hipMemAccessDesc access = {};
+    access.location = prop.location;
+    access.flags = hipMemAccessFlagsProtReadWrite;
+    for (size_t i = 0; i < n; ++i) {
+        hipMemGenericAllocationHandle_t h;
+        if ((e = hipMemCreate(&h, pl.chunk, &prop, 0)) != hipSuccess) break;
+        pl.handles.push_back(h);
+        pl.mapped.push_back(false);
+        char *p = static_cast<char *>(va) + i * pl.chunk;
+        if ((e = hipMemMap(p, pl.chunk, 0, h, 0)) != hipSuccess) break;
+        pl.mapped[i] = true;
+        if ((e = hipMemSetAccess(p, pl.chunk, &access, 1)) != hipSuccess) break;
+    }
+    if (e != hipSuccess) {
+        pool_release(va, pl);
+        return hip_fail(e, "creating a pool (HIP virtual memory management)");
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_spread_mutex);
+        g_pools[va] = pl;
+    }
+    *base = va;
+    if (actual_bytes) *actual_bytes = (int64_t)(n * pl.chunk);
+    if (actual_chunk_bytes) *actual_chunk_bytes = (int64_t)pl.chunk;
+    return LAA_OK;
+}
+
+int laa_pool_trim(void *base, int32_t n_ranges, const int64_t *offsets, const int64_t *lengths)
+{
+    if (!base || n_ranges < 0 || (n_ranges > 0 && (!offsets || !lengths))) return fail(LAA_EINVAL, "bad arguments");
+    std::lock_guard<std::mutex> lock(g_spread_mutex);
+    auto it = g_pools.find(base);
+    if (it == g_pools.end()) return fail(LAA_EINVAL, "not a pointer returned by laa_pool_create");
+    Pool &pl = it->second;
+    std::vector<bool> keep(pl.handles.size(), false);
+    for (int32_t r = 0; r < n_ranges; ++r) {
+        if (offsets[r] < 0 || lengths[r] <= 0 || (size_t)offsets[r] + (size_t)lengths[r] > pl.reserved)
+            return fail(LAA_EINVAL, "range %d lies outside the pool", r);
+        for (size_t c = (size_t)offsets[r] / pl.chunk; c <= ((size_t)offsets[r] + (size_t)lengths[r] - 1) / pl.chunk; ++c) {
+            if (!pl.mapped[c]) return fail(LAA_EINVAL, "range %d touches a chunk that was released earlier", r);
+            keep[c] = true;
+        }
+    }
+    hipError_t e = hipDeviceSynchronize();                  // nothing may still be using what goes away
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize before trimming a pool");
+    for (size_t c = 0; c < pl.handles.size(); ++c) {
+        if (keep[c] || !pl.mapped[c]) continue;
+        (void)hipMemUnmap(static_cast<char *>(base) + c * pl.chunk, pl.chunk);
+        (void)hipMemRelease(pl.handles[c]);
+        pl.mapped[c] = false;
+        pl.handles[c] = hipMemGenericAllocationHandle_t();
+    }
+    return LAA_OK;
+}
+
+int laa_pool_free(void *base)
+{
+    if (!base) return LAA_OK;
+    Pool pl;
+    {
+        std::lock_guard<std::mutex> lock(g_spread_mutex);
+        auto it = g_pools.find(base);
+        if (it == g_pools.end()) return fail(LAA_EINVAL, "not a pointer returned by laa_pool_create");
+        pl = it->second;
+        g_pools.erase(it);
+    }
+    hipError_t e = hipDeviceSynchronize();
+    pool_release(base, pl);
+    return e == hipSuccess ? LAA_OK : hip_fail(e, "hipDeviceSynchronize before freeing a pool");
+}
+
 int laa_debug_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t *out)
 {
     if (!ctr || !key || !out) return fail(LAA_EINVAL, "null argument");

@@ -32,6 +32,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #ifndef LAA_NT_STORE
 #define LAA_NT_STORE true    // non-temporal stores of streamed state
 #endif
+#ifndef LAA_PERSIST_WAVES
+#define LAA_PERSIST_WAVES 8  // resident one-wavefront blocks per CU of the persistent experiment
+#endif
 // Dense kernels run one wavefront per thread block: with 16 to 35 independent 16-byte streams per thread the
 // finest dispatch granularity measured fastest (64 > 128 > 256 > 512 threads, about 5 % end to end at d = 4e8).
 static constexpr int DBLOCK = LAA_BLOCK;
@@ -295,6 +298,74 @@ __global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
         step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT, TDEV>(a, j, w_begin, w_end);
 }
 
+#if defined(LAA_PERSIST)
+// EXPERIMENT (build flag LAA_PERSIST = 1: grid-stride loop; 2: the next tile's loads are issued before the current
+// tile is computed and stored).  A fixed grid of one-wavefront blocks strides over the column groups.
+template <int WT> struct Tile { Pack<4> av, xs, sn, xv[WT], bv[WT]; };
+
+template <int WT, int GS>
+__device__ __forceinline__ void tile_load(const StepArgs &a, const int64_t j, Tile<WT> &t)
+{
+    if constexpr (GS != GRAD_EXPLICIT) t.av = ld<4, false>(a.a + j);
+    if constexpr (GS == GRAD_QUADRATIC) t.xs = ld<4, false>(a.xstar + j);
+    t.sn = ld<4, false>(a.snap + j);
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+        t.xv[i] = ld<4, NT_LD>(a.x + (int64_t)i * a.pitch + j);
+        t.bv[i] = ld<4, NT_LD>(a.acc + (int64_t)i * a.pitch + j);
+    }
+}
+
+template <int WT, int GS, int OS>
+__device__ __forceinline__ void tile_step_store(const StepArgs &a, const int64_t j, Tile<WT> &t)
+{
+    Pack<4> step;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) step.v[e] = a.eta / sqrtf(t.sn.v[e] + a.pad);
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+        const int64_t row = (int64_t)i * a.pitch + j;
+        const Pack<4> g = gradient<4, GS, OS, false>(a, j, row, i, t.xv[i], t.av, t.xs);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            t.xv[i].v[e] = fmaf(-g.v[e], step.v[e], t.xv[i].v[e]);
+            t.bv[i].v[e] = fmaf(g.v[e], g.v[e], t.bv[i].v[e]);
+        }
+        st<4, NT_ST>(a.x + row, t.xv[i]);
+        st<4, NT_ST>(a.acc + row, t.bv[i]);
+    }
+}
+
+template <int WT, int GS, int OS>
+__global__ __launch_bounds__(DBLOCK) void step_persist_kernel(const StepArgs a)
+{
+    const int64_t n_groups = a.d >> 2;
+    const int64_t stride = (int64_t)gridDim.x * DBLOCK;
+    int64_t q = (int64_t)blockIdx.x * DBLOCK + threadIdx.x;
+#if LAA_PERSIST == 1
+    for (; q < n_groups; q += stride) {
+        Tile<WT> t;
+        tile_load<WT, GS>(a, q * 4, t);
+        tile_step_store<WT, GS, OS>(a, q * 4, t);
+    }
+#else
+    if (q >= n_groups) return;
+    Tile<WT> cur;
+    tile_load<WT, GS>(a, q * 4, cur);
+    for (;;) {
+        const int64_t qn = q + stride;
+        const bool more = qn < n_groups;
+        Tile<WT> nxt;
+        if (more) tile_load<WT, GS>(a, qn * 4, nxt);
+        tile_step_store<WT, GS, OS>(a, q * 4, cur);
+        if (!more) break;
+        cur = nxt;
+        q = qn;
+    }
+#endif
+}
+#endif  // LAA_PERSIST
+
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
 // shared iterate kept in every worker's row.  Algorithm 2 (Local SGD): y = x - eta G per worker.
 // ROW0 (Algorithm 1 with lazy replicas): the one iterate is read from and written to row 0 of x only, B2 to snap only.
@@ -486,6 +557,17 @@ static inline hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t
             if constexpr (WT == 1) LAA_STEP(false, false, true, false, false);
             else return hipErrorInvalidValue;
         } else {
+#if defined(LAA_PERSIST)
+            if constexpr (VEC == 4 && GS != GRAD_EXPLICIT) {
+                if (a.W == WT) {
+                    const int64_t want = (a.d / 4 + DBLOCK - 1) / DBLOCK;
+                    const int64_t cap = 256 * (int64_t)LAA_PERSIST_WAVES;
+                    hipLaunchKernelGGL((step_persist_kernel<WT, GS, OS>), dim3((unsigned)(want < cap ? want : cap)),
+                                       dim3(DBLOCK), 0, s, a);
+                    return hipGetLastError();
+                }
+            }
+#endif
             LAA_STEP(false, false, false, false, false);
         }
     } else if (a.algo == ALGO_DIST_ADAGRAD) {

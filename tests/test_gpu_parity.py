@@ -208,6 +208,57 @@ def test_spread_buffers_layout(B, hold_gaps):
         B.spread_buffers(d, W, d - 4)
 
 
+def test_pool_and_measured_placement(B):
+    """binding.Pool (laa_pool_create / trim / free) and placement.tune: arrays at offsets of a chunked pool, the step
+    timed on candidate placements, the chunks of the winner kept and the rest released; results as with ordinary
+    tensors, bit for bit."""
+    import torch
+    from paper_1911_09030_amd import placement
+    W, d, H = 4, 4 * 64 * 33, 3
+    chunk = 2 << 20
+    free0 = torch.cuda.mem_get_info()[0]
+    pool = B.Pool(40 * chunk, chunk_bytes=chunk)
+    assert pool.nbytes == 40 * chunk and pool.chunk_bytes == chunk
+    assert free0 - torch.cuda.mem_get_info()[0] >= 40 * chunk
+    timed = []
+
+    def measure(mats, vecs, pitch):
+        m = placement.quadratic_step_timer(d, W, 0.5, 1.0, 5, B.OFF_PHILOX, 0.1, 0.1)(mats, vecs, pitch)
+        timed.append(m)
+        return m
+
+    best = placement.tune(pool, d, W, 2, 3, measure, n_random=6, seed=1)
+    assert best.tried == len(timed) - 3 and best.ms > 0 and best.pitch >= d and best.pitch % 1024 == 0
+    spans = sorted(best.ranges(d, W))
+    assert all(a + n <= b for (a, n), (b, _) in zip(spans, spans[1:])), "arrays overlap"
+    (x, acc), (snap, a, xs) = placement.views(pool, d, W, best)
+    pool.trim(best.ranges(d, W))
+    kept = {c for o, n in best.ranges(d, W) for c in range(4 * o // chunk, (4 * (o + n) - 1) // chunk + 1)}
+    assert free0 - torch.cuda.mem_get_info()[0] < (len(kept) + 2) * chunk + (64 << 20)      # the rest went back
+    rng = np.random.default_rng(37)
+    an = rng.uniform(0.1, 10, d).astype(np.float32); xn = rng.standard_normal(d).astype(np.float32)
+    a.copy_(torch.from_numpy(an)); xs.copy_(torch.from_numpy(xn))
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0, x=x, acc=acc, snap=snap, pitch=best.pitch); g.set_lazy_replicas(True); g.init_state()
+    g.set_generator(B.GEN_QUADRATIC, 5, a, xs, None, B.OFF_PHILOX, 0.1, 0.1)
+    r = B.LocalAdaAlter(d, W, H, 0.5, 1.0); r.set_lazy_replicas(True); r.init_state()
+    r.set_generator(B.GEN_QUADRATIC, 5, dev(an), dev(xn), None, B.OFF_PHILOX, 0.1, 0.1)
+    for _ in range(2 * H + 1):
+        g.step_gen(); r.step_gen()
+    torch.cuda.synchronize()
+    assert torch.equal(g.x, r.x) and torch.equal(g.acc, r.acc) and torch.equal(g.snap, r.snap)
+    with pytest.raises(B.LaaError):
+        pool.trim([(0, pool.nbytes // 4 + 1)])                       # outside the pool
+    with pytest.raises(ValueError):
+        pool.tensor(pool.nbytes // 4 - 10, (64,))
+    with pytest.raises(B.LaaError):
+        B._check(B.lib().laa_pool_free(B.C.c_void_p(12345 << 21)))   # not one of ours
+    del g, x, acc, snap, a, xs
+    pool.close()
+    assert pool.base is None
+    with pytest.raises(ValueError):
+        placement.tune(B.Pool(chunk, chunk_bytes=chunk), 1 << 20, W, 2, 3, measure)     # too small for the arrays
+
+
 def test_fused_step_equals_local_step_plus_sync(B):
     import torch
     W, H, d = 8, 3, D_SMALL
@@ -1079,11 +1130,18 @@ def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
     o.set_generator(oracle.GEN_QUADRATIC, c.seed, a[cols], xs[cols], None, om, c.noise_scale, c.off_scale)
     o.sample_a, o.sample_xs = a[cols], xs[cols]
     if bench_layout:
+        # as bench.py sets the workload up: arrays at a measured placement inside a pool of most of the free memory
+        # (fewer candidates here), the rest of the pool released, lazy replicas on
         import torch
-        rd = max(wl.SPREAD_ROW_DISTANCE, c.d)
-        backing, bx, bacc, bsnap, da, dxs, rp = B.spread_buffers(c.d, c.W, rd)
-        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=rp)
-        g._keep_backing = backing
+        from paper_1911_09030_amd import placement
+        pool = B.Pool(int(torch.cuda.mem_get_info()[0] * 0.9))
+        measure = placement.quadratic_step_timer(c.d, c.W, c.eta, c.eps, c.seed, om, c.noise_scale, c.off_scale)
+        best = placement.tune(pool, c.d, c.W, 2, 3, measure, n_random=8, seed=c.seed)
+        (bx, bacc), (bsnap, da, dxs) = placement.views(pool, c.d, c.W, best)
+        pool.trim(best.ranges(c.d, c.W))
+        say(f"   placement: {best.tried} timed, best {best.ms:.3f} ms, slowest {best.slowest_ms:.3f} ms")
+        g = B.LocalAdaAlter(c.d, c.W, c.H, c.eta, c.eps, x=bx, acc=bacc, snap=bsnap, pitch=best.pitch)
+        g._keep_backing = pool
         g.set_lazy_replicas(True)
         da.copy_(torch.from_numpy(a)); dxs.copy_(torch.from_numpy(xs))
     else:
