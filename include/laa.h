@@ -140,7 +140,8 @@ int laa_local_step_dense(laa_handle h, const float *grads);
  * j and w are global indices (laa_set_shard), t the 1-based iteration.  off_mode
  * LAA_OFF_PHILOX regenerates off_wj = off_scale * normal from the same counter
  * with t = 0 and 2 in place of 3 instead of reading an array; LAA_OFF_ARRAY reads
- * off; LAA_OFF_NONE uses zero. */
+ * off; LAA_OFF_NONE uses zero.  noise_scale and off_scale are standard deviations:
+ * finite and >= 0 (LAA_EINVAL otherwise). */
 int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a, const float *xstar,
                       const float *off, int32_t off_mode, float noise_scale, float off_scale);
 

@@ -469,6 +469,8 @@ int laa_set_generator(laa_handle h, int32_t mode, uint64_t seed, const float *a,
     if (mode == LAA_GEN_NOISE) off_mode = LAA_OFF_NONE;
     if (off_mode < LAA_OFF_NONE || off_mode > LAA_OFF_PHILOX) return fail(LAA_EMODE, "unknown offset mode %d", off_mode);
     if (off_mode == LAA_OFF_ARRAY && !off) return fail(LAA_EINVAL, "null off with LAA_OFF_ARRAY");
+    if (!(noise_scale >= 0.0f) || !(off_scale >= 0.0f) || !std::isfinite(noise_scale) || !std::isfinite(off_scale))
+        return fail(LAA_EINVAL, "noise_scale and off_scale are standard deviations: finite and >= 0");
     const bool a16 = aligned(a, 16) && (!xstar || aligned(xstar, 16)) && (off_mode != LAA_OFF_ARRAY || aligned(off, 16));
     if (!aligned(a, 4) || (xstar && !aligned(xstar, 4)) || (off && !aligned(off, 4)))
         return fail(LAA_EALIGN, "generator array not 4-byte aligned");

@@ -32,9 +32,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #ifndef LAA_NT_STORE
 #define LAA_NT_STORE true    // non-temporal stores of streamed state
 #endif
-#ifndef LAA_PERSIST_WAVES
-#define LAA_PERSIST_WAVES 8  // resident one-wavefront blocks per CU of the persistent experiment
-#endif
 // Dense kernels run one wavefront per thread block: with 16 to 35 independent 16-byte streams per thread the
 // finest dispatch granularity measured fastest (64 > 128 > 256 > 512 threads, about 5 % end to end at d = 4e8).
 static constexpr int DBLOCK = LAA_BLOCK;
@@ -68,6 +65,18 @@ template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const P
     }
 }
 
+// The same with the address split into a part that is uniform over the wavefront (kernel arguments, block index:
+// held in scalar registers) and a small per-lane element offset: the load/store then takes the scalar base and a
+// 32-bit vector offset, and no per-lane 64-bit address arithmetic is needed.
+template <int VEC, bool NT> __device__ __forceinline__ Pack<VEC> ld(const float *base, uint32_t lane_off)
+{
+    return ld<VEC, NT>(base + lane_off);
+}
+template <int VEC, bool NT> __device__ __forceinline__ void st(float *base, uint32_t lane_off, const Pack<VEC> &r)
+{
+    st<VEC, NT>(base + lane_off, r);
+}
+
 // ------------------------------------------------------------------------------------------
 // Thread block -> work.  A tile is DBLOCK * VEC consecutive columns (one group per thread).
 //   joint: block b owns tile b for all W workers (needed when the step also averages over the workers).
@@ -77,7 +86,7 @@ template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const P
 //          in time, so those re-reads hit that XCD's L2 and HBM traffic stays at the algorithmic bytes:
 //              b -> lo = b mod 8, w = (b div 8) mod W, hi = b div 8W, tile = 8 hi + lo.
 template <int VEC, bool SPLIT>
-__device__ __forceinline__ bool block_work(int64_t d, int32_t W, int64_t *j, int32_t *w_begin, int32_t *w_end)
+__device__ __forceinline__ bool block_work(int64_t d, int32_t W, int64_t *jb, uint32_t *jl, int32_t *w_begin, int32_t *w_end)
 {
     int64_t tile;
     if constexpr (SPLIT) {
@@ -91,8 +100,9 @@ __device__ __forceinline__ bool block_work(int64_t d, int32_t W, int64_t *j, int
         *w_begin = 0;
         *w_end = W;
     }
-    *j = (tile * DBLOCK + threadIdx.x) * VEC;
-    return *j < d;
+    *jb = tile * (DBLOCK * VEC);                 // first column of the block: uniform
+    *jl = threadIdx.x * VEC;                     // this thread's column group within it
+    return *jb + *jl < d;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -126,65 +136,74 @@ __device__ __forceinline__ float u01(uint32_t r)
     return __uint_as_float(__builtin_amdgcn_alignbit(0x7Fu, r, 9u)) - 0x1.fffffep-1f;
 }
 
-// Four standard normals for the coordinates 4*qa .. 4*qa+3 of worker w at iteration word t on a stream.
-// Box-Muller on (u0,u1) and (u2,u3).
-__device__ __forceinline__ void normals4(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream, uint64_t qa, uint32_t w,
-                                         uint32_t t, float (&n)[4])
+// Four normals for the coordinates 4*qa .. 4*qa+3 of worker w at iteration word t on a stream, scaled by sigma and
+// left in factored form: normal e is rad[e / 2] * trig[e] (Box-Muller on (u0,u1) and (u2,u3): radius times cosine,
+// radius times sine), so that the caller can put the product into a multiply-add.  c = -2 ln2 sigma^2:
+// sigma sqrt(-2 ln u0) = sqrt(c log2 u0) for sigma >= 0, which saves the multiplication by sigma.
+struct Normals4 { float rad[2], trig[4]; };
+
+static constexpr float UNIT_NORMAL_C = -1.3862943611198906f;         // -2 ln 2
+
+__device__ __forceinline__ Normals4 normals4(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream, uint64_t qa, uint32_t w,
+                                             uint32_t t, float c)
 {
     uint32_t r[4];
     philox4x32_10((uint32_t)qa, w, t, stream + (uint32_t)(qa >> 32) * 16u, seed_lo, seed_hi, r);
+    Normals4 n;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const float u0 = u01(r[2 * p]), u1 = u01(r[2 * p + 1]);
-        // sqrt(-2 ln u0) = sqrt(-2 ln2 * log2 u0); u0 >= 2^-24 is a normal number, so the bare hardware
-        // log2 / sqrt apply (relative error 1.4e-7 over all 2^23 inputs); the hardware sine and cosine take
-        // their argument in turns, which is u1 itself (absolute error 1.3e-7 over all 2^23 inputs).
-        const float rad = __builtin_amdgcn_sqrtf(__builtin_amdgcn_logf(u0) * -1.3862943611198906f);
-        n[2 * p] = rad * __builtin_amdgcn_cosf(u1);
-        n[2 * p + 1] = rad * __builtin_amdgcn_sinf(u1);
+        // u0 >= 2^-24 is a normal number, so the bare hardware log2 / sqrt apply (relative error 1.4e-7 over all 2^23
+        // inputs); the hardware sine and cosine take their argument in turns, which is u1 itself (absolute error
+        // 1.3e-7 over all 2^23 inputs).
+        n.rad[p] = __builtin_amdgcn_sqrtf(__builtin_amdgcn_logf(u0) * c);
+        n.trig[2 * p] = __builtin_amdgcn_cosf(u1);
+        n.trig[2 * p + 1] = __builtin_amdgcn_sinf(u1);
     }
+    return n;
 }
 
 static constexpr uint32_t STREAM_OFFSET = 2, STREAM_NOISE = 3;
 
-// Gradient of worker w for the VEC coordinates starting at j, evaluated at xv (the worker's x before the step).
+// Gradient of worker w for the VEC coordinates starting at j = jb + jl, evaluated at xv (the worker's x before the
+// step); rowb = w * pitch + jb is the uniform part of the element's index in the [W][pitch] arrays.
 //   quadratic: g = a (x - (xstar + off)) + noise_scale n        noise: g = a n
+// evaluated as a ((x - xstar) - off) + noise_scale n with the scales folded into the normals' radii.
 // TDEV: the iteration number is t_lo plus a device word (periods replayed from a graph).
 template <int VEC, int GS, int OS, bool TDEV = false>
-__device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t j, int64_t row, int32_t w,
+__device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t jb, uint32_t jl, int64_t rowb, int32_t w,
                                               const Pack<VEC> &xv, const Pack<VEC> &av, const Pack<VEC> &xs)
 {
     Pack<VEC> g;
     if constexpr (GS == GRAD_EXPLICIT) {
-        g = ld<VEC, NT_LD>(a.grads + row);
+        g = ld<VEC, NT_LD>(a.grads + rowb, jl);
     } else {
-        const uint64_t qa = (uint64_t)(j + a.col0) >> 2;      // col0 % 4 == 0: j & 3 is the global lane too
+        const uint64_t ja = (uint64_t)(jb + jl + a.col0);    // col0 % 4 == 0: ja & 3 is the lane within the Philox block
+        const uint64_t qa = ja >> 2;
         const uint32_t wg = (uint32_t)(w + a.w0);
-        float n[4];
         uint32_t t = a.t_lo;
         if constexpr (TDEV) t += *a.t_dev;                       // uniform: one scalar load
-        normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, wg, t, n);
+        const Normals4 n = normals4(a.seed_lo, a.seed_hi, STREAM_NOISE, qa, wg, t, GS == GRAD_NOISE ? UNIT_NORMAL_C : a.noise_c);
+        const int lane0 = VEC == 4 ? 0 : (int)(ja & 3);
         if constexpr (GS == GRAD_NOISE) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) g.v[e] = av.v[e] * n[VEC == 4 ? e : (int)(j & 3)];
+            for (int e = 0; e < VEC; ++e) g.v[e] = av.v[e] * (n.rad[(lane0 + e) >> 1] * n.trig[lane0 + e]);
         } else {
-            Pack<VEC> o;
+            Pack<VEC> diff;                                      // x - xstar - off
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) diff.v[e] = xv.v[e] - xs.v[e];
             if constexpr (OS == OFFSET_ARRAY) {
-                o = ld<VEC, NT_LD>(a.off + row);
+                const Pack<VEC> o = ld<VEC, NT_LD>(a.off + rowb, jl);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) diff.v[e] = diff.v[e] - o.v[e];
             } else if constexpr (OS == OFFSET_PHILOX) {
-                float m[4];
-                normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, wg, 0u, m);
+                const Normals4 m = normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, qa, wg, 0u, a.off_c);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) o.v[e] = a.off_scale * m[VEC == 4 ? e : (int)(j & 3)];
-            } else {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) o.v[e] = 0.0f;
+                for (int e = 0; e < VEC; ++e) diff.v[e] = fmaf(-m.rad[(lane0 + e) >> 1], m.trig[lane0 + e], diff.v[e]);
             }
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const float nz = n[VEC == 4 ? e : (int)(j & 3)];
-                g.v[e] = fmaf(av.v[e], xv.v[e] - (xs.v[e] + o.v[e]), a.noise_scale * nz);
-            }
+            for (int e = 0; e < VEC; ++e)
+                g.v[e] = fmaf(av.v[e], diff.v[e], n.rad[(lane0 + e) >> 1] * n.trig[lane0 + e]);
         }
     }
     return g;
@@ -216,18 +235,19 @@ template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const P
 //   CIN : the state is collapsed on entry: read x from row 0 and B2 from snap for every worker
 //   COUT: (with SYNC) leave it collapsed: write the means to row 0 of x and to snap only
 template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool CIN, bool COUT, bool TDEV>
-__device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, const int32_t w_begin,
+__device__ __forceinline__ void step_body(const StepArgs &a, const int64_t jb, const uint32_t jl, const int32_t w_begin,
                                           const int32_t w_end)
 {
+    // column j = jb + jl: jb is uniform over the block, jl the lane's offset (addresses = scalar base + lane offset)
     Pack<VEC> av, xs, step, sn, x0;
-    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
-    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
+    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + jb, jl);
+    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + jb, jl);
     if constexpr (!GRAD_ONLY) {
-        sn = ld<VEC, false>(a.snap + j);
+        sn = ld<VEC, false>(a.snap + jb, jl);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) step.v[e] = a.eta / sqrtf(sn.v[e] + a.pad);
     }
-    if constexpr (CIN) x0 = ld<VEC, false>(a.x + j);
+    if constexpr (CIN) x0 = ld<VEC, false>(a.x + jb, jl);
 
     Pack<VEC> sx, sb;
 #pragma unroll
@@ -237,21 +257,21 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
         Pack<VEC> xv[WT], bv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
+            const int64_t rowb = (int64_t)(w0 + i) * a.pitch + jb;
             if constexpr (CIN) {
                 xv[i] = x0;
                 if constexpr (!GRAD_ONLY) bv[i] = sn;
             } else {
-                if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, NT_LD>(a.x + row);
-                if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, NT_LD>(a.acc + row);
+                if constexpr (GS == GRAD_QUADRATIC || !GRAD_ONLY) xv[i] = ld<VEC, NT_LD>(a.x + rowb, jl);
+                if constexpr (!GRAD_ONLY) bv[i] = ld<VEC, NT_LD>(a.acc + rowb, jl);
             }
         }
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            const int64_t row = (int64_t)(w0 + i) * a.pitch + j;
-            const Pack<VEC> g = gradient<VEC, GS, OS, TDEV>(a, j, row, w0 + i, xv[i], av, xs);
+            const int64_t rowb = (int64_t)(w0 + i) * a.pitch + jb;
+            const Pack<VEC> g = gradient<VEC, GS, OS, TDEV>(a, jb, jl, rowb, w0 + i, xv[i], av, xs);
             if constexpr (GRAD_ONLY) {
-                st<VEC, NT_ST>(a.grad_out + row, g);
+                st<VEC, NT_ST>(a.grad_out + rowb, jl, g);
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
@@ -259,8 +279,8 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
                     bv[i].v[e] = fmaf(g.v[e], g.v[e], bv[i].v[e]);
                 }
                 if constexpr (!SYNC) {
-                    st<VEC, NT_ST>(a.x + row, xv[i]);
-                    st<VEC, NT_ST>(a.acc + row, bv[i]);
+                    st<VEC, NT_ST>(a.x + rowb, jl, xv[i]);
+                    st<VEC, NT_ST>(a.acc + rowb, jl, bv[i]);
                 }
             }
         }
@@ -275,107 +295,60 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t j, co
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
         if constexpr (COUT) {
-            st<VEC, false>(a.x + j, sx);
+            st<VEC, false>(a.x + jb, jl, sx);
         } else {
             for (int32_t w = 0; w < a.W; ++w) {
-                const int64_t row = (int64_t)w * a.pitch + j;
-                st<VEC, NT_ST>(a.x + row, sx);
-                st<VEC, NT_ST>(a.acc + row, sb);
+                const int64_t rowb = (int64_t)w * a.pitch + jb;
+                st<VEC, NT_ST>(a.x + rowb, jl, sx);
+                st<VEC, NT_ST>(a.acc + rowb, jl, sb);
             }
         }
-        st<VEC, false>(a.snap + j, sb);
+        st<VEC, false>(a.snap + jb, jl, sb);
     }
+}
+
+// Most wavefronts per SIMD for the steps that stream all 2W rows in and out (no averaging, state not collapsed): they
+// need 122 (generated gradient) and 108 (explicit gradient) vector registers, which would allow 4, but fewer
+// wavefronts with the same loads in flight run faster on a saturated memory system.  Measured at d = 4e8 / 1e8, W = 8,
+// same process sequence: generated gradient 8.69 ms with 3, 8.75 with 4, 8.76 with 2; explicit gradient 2.56 ms
+// with 2, 2.59 with 4, 2.60 with 3.
+#ifndef LAA_PLAIN_WAVES
+#define LAA_PLAIN_WAVES 3
+#endif
+#ifndef LAA_EXPLICIT_WAVES
+#define LAA_EXPLICIT_WAVES 2
+#endif
+// The steps around an averaging (fewer bytes, bound by the generator's arithmetic as much as by memory) showed no
+// consistent preference between 2 and 5 wavefronts per SIMD and are left to the register count.
+static constexpr int step_waves(int gs, bool sync, bool grad_only, bool cin)
+{
+    return (sync || grad_only || cin) ? 8 : gs == GRAD_EXPLICIT ? LAA_EXPLICIT_WAVES : LAA_PLAIN_WAVES;
 }
 
 template <int VEC, int WT, int GS, int OS, bool SYNC, bool GRAD_ONLY, bool SPLIT, bool CIN, bool COUT, bool TDEV = false>
-__global__ __launch_bounds__(DBLOCK) void step_kernel(const StepArgs a)
+__global__ __launch_bounds__(DBLOCK)
+__attribute__((amdgpu_waves_per_eu(1, step_waves(GS, SYNC, GRAD_ONLY, CIN))))
+void step_kernel(const StepArgs a)
 {
     static_assert(!SPLIT || (WT == 1 && !SYNC), "a split block owns one worker and cannot average");
     static_assert(!COUT || SYNC, "only a step that averages can leave the state collapsed");
-    int64_t j;
+    int64_t jb;
+    uint32_t jl;
     int32_t w_begin, w_end;
-    if (block_work<VEC, SPLIT>(a.d, a.W, &j, &w_begin, &w_end))
-        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT, TDEV>(a, j, w_begin, w_end);
+    if (block_work<VEC, SPLIT>(a.d, a.W, &jb, &jl, &w_begin, &w_end))
+        step_body<VEC, WT, GS, OS, SYNC, GRAD_ONLY, CIN, COUT, TDEV>(a, jb, jl, w_begin, w_end);
 }
-
-#if defined(LAA_PERSIST)
-// EXPERIMENT (build flag LAA_PERSIST = 1: grid-stride loop; 2: the next tile's loads are issued before the current
-// tile is computed and stored).  A fixed grid of one-wavefront blocks strides over the column groups.
-template <int WT> struct Tile { Pack<4> av, xs, sn, xv[WT], bv[WT]; };
-
-template <int WT, int GS>
-__device__ __forceinline__ void tile_load(const StepArgs &a, const int64_t j, Tile<WT> &t)
-{
-    if constexpr (GS != GRAD_EXPLICIT) t.av = ld<4, false>(a.a + j);
-    if constexpr (GS == GRAD_QUADRATIC) t.xs = ld<4, false>(a.xstar + j);
-    t.sn = ld<4, false>(a.snap + j);
-#pragma unroll
-    for (int i = 0; i < WT; ++i) {
-        t.xv[i] = ld<4, NT_LD>(a.x + (int64_t)i * a.pitch + j);
-        t.bv[i] = ld<4, NT_LD>(a.acc + (int64_t)i * a.pitch + j);
-    }
-}
-
-template <int WT, int GS, int OS>
-__device__ __forceinline__ void tile_step_store(const StepArgs &a, const int64_t j, Tile<WT> &t)
-{
-    Pack<4> step;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) step.v[e] = a.eta / sqrtf(t.sn.v[e] + a.pad);
-#pragma unroll
-    for (int i = 0; i < WT; ++i) {
-        const int64_t row = (int64_t)i * a.pitch + j;
-        const Pack<4> g = gradient<4, GS, OS, false>(a, j, row, i, t.xv[i], t.av, t.xs);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            t.xv[i].v[e] = fmaf(-g.v[e], step.v[e], t.xv[i].v[e]);
-            t.bv[i].v[e] = fmaf(g.v[e], g.v[e], t.bv[i].v[e]);
-        }
-        st<4, NT_ST>(a.x + row, t.xv[i]);
-        st<4, NT_ST>(a.acc + row, t.bv[i]);
-    }
-}
-
-template <int WT, int GS, int OS>
-__global__ __launch_bounds__(DBLOCK) void step_persist_kernel(const StepArgs a)
-{
-    const int64_t n_groups = a.d >> 2;
-    const int64_t stride = (int64_t)gridDim.x * DBLOCK;
-    int64_t q = (int64_t)blockIdx.x * DBLOCK + threadIdx.x;
-#if LAA_PERSIST == 1
-    for (; q < n_groups; q += stride) {
-        Tile<WT> t;
-        tile_load<WT, GS>(a, q * 4, t);
-        tile_step_store<WT, GS, OS>(a, q * 4, t);
-    }
-#else
-    if (q >= n_groups) return;
-    Tile<WT> cur;
-    tile_load<WT, GS>(a, q * 4, cur);
-    for (;;) {
-        const int64_t qn = q + stride;
-        const bool more = qn < n_groups;
-        Tile<WT> nxt;
-        if (more) tile_load<WT, GS>(a, qn * 4, nxt);
-        tile_step_store<WT, GS, OS>(a, q * 4, cur);
-        if (!more) break;
-        cur = nxt;
-        q = qn;
-    }
-#endif
-}
-#endif  // LAA_PERSIST
 
 // Algorithm 1 (Distributed AdaGrad): G = mean_i G_i; B2 += G o G; x -= eta G / sqrt(B2 + eps^2), one
 // shared iterate kept in every worker's row.  Algorithm 2 (Local SGD): y = x - eta G per worker.
 // ROW0 (Algorithm 1 with lazy replicas): the one iterate is read from and written to row 0 of x only, B2 to snap only.
 template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC, bool ROW0>
-__device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j)
+__device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t jb, const uint32_t jl)
 {
     static_assert(!ROW0 || ALGO == ALGO_DIST_ADAGRAD, "only Algorithm 1 has a single iterate");
     Pack<VEC> av, xs;
-    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + j);
-    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + j);
+    if constexpr (GS != GRAD_EXPLICIT) av = ld<VEC, false>(a.a + jb, jl);
+    if constexpr (GS == GRAD_QUADRATIC) xs = ld<VEC, false>(a.xstar + jb, jl);
     Pack<VEC> sg, sx;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) sg.v[e] = sx.v[e] = 0.0f;
@@ -384,17 +357,18 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
         Pack<VEC> xv[WT], gv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            if constexpr (ROW0) xv[i] = (w0 == 0 && i == 0) ? ld<VEC, false>(a.x + j) : x0;
-            else xv[i] = ld<VEC, NT_LD>(a.x + (int64_t)(w0 + i) * a.pitch + j);
+            if constexpr (ROW0) xv[i] = (w0 == 0 && i == 0) ? ld<VEC, false>(a.x + jb, jl) : x0;
+            else xv[i] = ld<VEC, NT_LD>(a.x + ((int64_t)(w0 + i) * a.pitch + jb), jl);
             if (w0 == 0 && i == 0) x0 = xv[0];
         }
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            gv[i] = gradient<VEC, GS, OS>(a, j, (int64_t)(w0 + i) * a.pitch + j, w0 + i, xv[i], av, xs);
+            const int64_t rowb = (int64_t)(w0 + i) * a.pitch + jb;
+            gv[i] = gradient<VEC, GS, OS>(a, jb, jl, rowb, w0 + i, xv[i], av, xs);
             if constexpr (ALGO == ALGO_LOCAL_SGD) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) xv[i].v[e] = fmaf(-a.eta, gv[i].v[e], xv[i].v[e]);
-                if constexpr (!SYNC) st<VEC, NT_ST>(a.x + (int64_t)(w0 + i) * a.pitch + j, xv[i]);
+                if constexpr (!SYNC) st<VEC, NT_ST>(a.x + rowb, jl, xv[i]);
             }
         }
         if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
@@ -409,7 +383,7 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
     }
     const float fw = (float)a.W;
     if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
-        Pack<VEC> b2 = ld<VEC, false>(a.snap + j);
+        Pack<VEC> b2 = ld<VEC, false>(a.snap + jb, jl);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float g = sg.v[e] / fw;
@@ -417,33 +391,34 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
             x0.v[e] = x0.v[e] - (a.eta * g) / sqrtf(b2.v[e] + a.eps2);
         }
         if constexpr (ROW0) {
-            st<VEC, false>(a.x + j, x0);
+            st<VEC, false>(a.x + jb, jl, x0);
         } else {
             for (int32_t w = 0; w < a.W; ++w) {
-                st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, x0);
-                st<VEC, NT_ST>(a.acc + (int64_t)w * a.pitch + j, b2);
+                st<VEC, NT_ST>(a.x + ((int64_t)w * a.pitch + jb), jl, x0);
+                st<VEC, NT_ST>(a.acc + ((int64_t)w * a.pitch + jb), jl, b2);
             }
         }
-        st<VEC, false>(a.snap + j, b2);
+        st<VEC, false>(a.snap + jb, jl, b2);
     } else if constexpr (SYNC) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) sx.v[e] = sx.v[e] / fw;
-        for (int32_t w = 0; w < a.W; ++w) st<VEC, NT_ST>(a.x + (int64_t)w * a.pitch + j, sx);
+        for (int32_t w = 0; w < a.W; ++w) st<VEC, NT_ST>(a.x + ((int64_t)w * a.pitch + jb), jl, sx);
     }
 }
 
 template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC, bool ROW0 = false>
 __global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
 {
-    int64_t j;
+    int64_t jb;
+    uint32_t jl;
     int32_t w_begin, w_end;
-    if (block_work<VEC, false>(a.d, a.W, &j, &w_begin, &w_end)) baseline_body<VEC, WT, GS, OS, ALGO, SYNC, ROW0>(a, j);
+    if (block_work<VEC, false>(a.d, a.W, &jb, &jl, &w_begin, &w_end)) baseline_body<VEC, WT, GS, OS, ALGO, SYNC, ROW0>(a, jb, jl);
 }
 
 // Synchronize branch on its own: x[w], acc[w] <- mean over w; snap <- mean acc.
 template <int VEC, int WT, bool X_ONLY, bool COUT>
 __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restrict__ acc, float *__restrict__ snap,
-                                          int64_t pitch, int32_t W, const int64_t j)
+                                          int64_t pitch, int32_t W, const int64_t jb, const uint32_t jl)
 {
     Pack<VEC> sx, sb;
 #pragma unroll
@@ -452,8 +427,8 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
         Pack<VEC> xv[WT], bv[WT];
 #pragma unroll
         for (int i = 0; i < WT; ++i) {
-            xv[i] = ld<VEC, NT_LD>(x + (int64_t)(w0 + i) * pitch + j);
-            if constexpr (!X_ONLY) bv[i] = ld<VEC, NT_LD>(acc + (int64_t)(w0 + i) * pitch + j);
+            xv[i] = ld<VEC, NT_LD>(x + ((int64_t)(w0 + i) * pitch + jb), jl);
+            if constexpr (!X_ONLY) bv[i] = ld<VEC, NT_LD>(acc + ((int64_t)(w0 + i) * pitch + jb), jl);
         }
         const Pack<VEC> tx = tree_sum<VEC, WT>(xv);
 #pragma unroll
@@ -468,24 +443,25 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
     if constexpr (COUT) {
-        st<VEC, false>(x + j, sx);
+        st<VEC, false>(x + jb, jl, sx);
     } else {
         for (int32_t w = 0; w < W; ++w) {
-            st<VEC, NT_ST>(x + (int64_t)w * pitch + j, sx);
-            if constexpr (!X_ONLY) st<VEC, NT_ST>(acc + (int64_t)w * pitch + j, sb);
+            st<VEC, NT_ST>(x + ((int64_t)w * pitch + jb), jl, sx);
+            if constexpr (!X_ONLY) st<VEC, NT_ST>(acc + ((int64_t)w * pitch + jb), jl, sb);
         }
     }
-    if constexpr (!X_ONLY) st<VEC, false>(snap + j, sb);
+    if constexpr (!X_ONLY) st<VEC, false>(snap + jb, jl, sb);
 }
 
 template <int VEC, int WT, bool X_ONLY, bool COUT>
 __global__ __launch_bounds__(DBLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                      float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W)
 {
-    int64_t j;
+    int64_t jb;
+    uint32_t jl;
     int32_t w_begin, w_end;
-    if (block_work<VEC, false>(d, W, &j, &w_begin, &w_end))
-        mean_body<VEC, WT, X_ONLY, COUT>(x, acc, snap, pitch, W, j);
+    if (block_work<VEC, false>(d, W, &jb, &jl, &w_begin, &w_end))
+        mean_body<VEC, WT, X_ONLY, COUT>(x, acc, snap, pitch, W, jb, jl);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -557,17 +533,6 @@ static inline hipError_t launch_step_4(const StepArgs &a, dim3 grid, hipStream_t
             if constexpr (WT == 1) LAA_STEP(false, false, true, false, false);
             else return hipErrorInvalidValue;
         } else {
-#if defined(LAA_PERSIST)
-            if constexpr (VEC == 4 && GS != GRAD_EXPLICIT) {
-                if (a.W == WT) {
-                    const int64_t want = (a.d / 4 + DBLOCK - 1) / DBLOCK;
-                    const int64_t cap = 256 * (int64_t)LAA_PERSIST_WAVES;
-                    hipLaunchKernelGGL((step_persist_kernel<WT, GS, OS>), dim3((unsigned)(want < cap ? want : cap)),
-                                       dim3(DBLOCK), 0, s, a);
-                    return hipGetLastError();
-                }
-            }
-#endif
             LAA_STEP(false, false, false, false, false);
         }
     } else if (a.algo == ALGO_DIST_ADAGRAD) {

@@ -25,7 +25,8 @@ struct StepArgs {
     float eta;           // eta_t of this iteration
     float pad;           // t' * eps^2
     float eps2;
-    float noise_scale, off_scale;
+    float noise_scale, off_scale;  // standard deviations of the noise and of the per-worker offsets (>= 0)
+    float noise_c, off_c;          // -2 ln2 sigma^2 of each: the normals' radii come out scaled (set by launch_step)
     uint32_t seed_lo, seed_hi;
     int64_t col0;        // global index of column 0 (multiple of 4) and
     int32_t w0;          // global index of worker 0: the generator's counters are global

@@ -113,26 +113,54 @@ def event_median_ms(step, n=5):
     return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
 
 
-def quadratic_step_timer(d, W, eta, eps, seed, off_mode, noise_scale, off_scale, tile=None):
-    """measure() for tune(): the plain generator step of the quadratic workload (no averaging in reach) on matrices
-    (x, acc[, stored offsets]) and vectors (snap, a, xstar) at a candidate placement.  The inputs are constants: the
-    step's duration does not depend on their values."""
+def generator_step_timer(d, W, eta, eps, seed, mode, off_mode, noise_scale, off_scale, tile=None):
+    """measure() for tune(): the plain generator step (no averaging in reach) on arrays at a candidate placement.
+    Quadratic mode: matrices (x, acc[, stored offsets]), vectors (snap, a, xstar); noise mode: matrices (x, acc),
+    vectors (snap, a).  The inputs are constants: the step's duration does not depend on their values."""
     from . import binding as B
 
     def measure(mats, vecs, pitch):
         vecs[1].fill_(1.0)
-        vecs[2].fill_(0.5)
+        xstar = None
+        if mode == B.GEN_QUADRATIC:
+            xstar = vecs[2]
+            xstar.fill_(0.5)
         off = None
         if off_mode == B.OFF_ARRAY:
             off = mats[2]
             off.zero_()
         h = B.LocalAdaAlter(d, W, 1 << 30, eta, eps, x=mats[0], acc=mats[1], snap=vecs[0], pitch=pitch)
         h.init_state()
-        h.set_generator(B.GEN_QUADRATIC, seed, vecs[1], vecs[2], off, off_mode, noise_scale, off_scale)
+        h.set_generator(mode, seed, vecs[1], xstar, off, off_mode, noise_scale, off_scale)
         if tile is not None:
             h.set_tile(tile)
         h.step_gen()
         ms = event_median_ms(h.step_gen)
+        h.close()
+        return ms
+
+    return measure
+
+
+def quadratic_step_timer(d, W, eta, eps, seed, off_mode, noise_scale, off_scale, tile=None):
+    from . import binding as B
+    return generator_step_timer(d, W, eta, eps, seed, B.GEN_QUADRATIC, off_mode, noise_scale, off_scale, tile)
+
+
+def averaging_timer(d, W, eta, eps):
+    """measure() for tune(): the Synchronize pass over the whole of x, acc, snap (matrices (x, acc), vectors
+    (snap,)): 2W read and 2W + 1 write streams, the pattern of the averaging of touched rows on a row-sparse table."""
+    from . import binding as B
+
+    def measure(mats, vecs, pitch):
+        h = B.LocalAdaAlter(d, W, 1 << 30, eta, eps, x=mats[0], acc=mats[1], snap=vecs[0], pitch=pitch)
+        h.init_state()
+
+        def one():
+            h.set_counters(1, 1)          # one local step pending, touched rows unknown: the next sync takes the whole table
+            h.sync()
+        one()
+        ms = event_median_ms(one)
         h.close()
         return ms
 
