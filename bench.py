@@ -51,6 +51,8 @@ def parse():
     p.add_argument("--no-lazy-replicas", action="store_true",
                    help="write the averaged state into all W rows at every sync (laa_set_lazy_replicas off)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-settle", action="store_true",
+                   help="do not wait for the driver's clearing of released memory before timing (profiler counter runs)")
     p.add_argument("--graph", action="store_true",
                    help="quadratic workloads: run whole periods through laa_run_periods_gen (one HIP graph per period, "
                         "replayed) on a side stream; for sizes where the launches dominate")
@@ -343,7 +345,7 @@ def main():
     # that runs meanwhile (measured: the step 0.7 % slower for up to 20 s after 240 GB were released).  Keep
     # stepping, untimed, until whole periods stop getting faster.
     settle = None
-    if spread and not args.graph:
+    if spread and not args.graph and not args.no_settle:
         # reference: what the tuner measured for the dominant kernel at the chosen placement (quadratic and explicit
         # workloads, whose first pool is the one the step runs on); otherwise wait for a plateau
         ref = tuning["pools"][0]["best_ms"] if tuning.get("pools") and c.kind != "embedding" else None

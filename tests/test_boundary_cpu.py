@@ -65,6 +65,8 @@ def test_host_error_paths(L):
     assert L.laa_set_generator(h, binding.GEN_QUADRATIC, 0, C.c_void_p(16), C.c_void_p(32), None,
                                binding.OFF_ARRAY, .1, .1) == binding.EINVAL
     assert L.laa_set_generator(h, binding.GEN_NOISE, 0, C.c_void_p(18), None, None, 0, .1, .1) == binding.EALIGN
+    assert L.laa_set_generator(h, binding.GEN_NOISE, 0, C.c_void_p(16), None, None, 0, -.1, .1) == binding.EINVAL   # a standard deviation
+    assert L.laa_set_generator(h, binding.GEN_QUADRATIC, 0, C.c_void_p(16), C.c_void_p(32), None, 0, .1, float("nan")) == binding.EINVAL
     assert L.laa_set_tile(h, 0) == binding.OK              # one worker per block in non-averaging steps
     assert L.laa_set_lazy_replicas(h, 1) == binding.OK
     assert L.laa_set_lazy_replicas(None, 1) == binding.EINVAL
@@ -93,7 +95,17 @@ def test_host_error_paths(L):
     assert L.laa_bytes_moved(h, C.byref(b), C.byref(lit)) == binding.OK and b.value == 0 and lit.value == 0
     assert L.laa_bytes_moved(h, None, C.byref(lit)) == binding.OK
     assert L.laa_bytes_moved(h, None, None) == binding.EINVAL
+    assert L.laa_sync_static(h) == binding.ENOTATTACHED
     assert L.laa_destroy(h) == binding.OK
+    # the chunked pool: argument checks happen before any device is touched
+    base = C.c_void_p()
+    assert L.laa_pool_create(0, 1 << 21, C.byref(base), None, None) == binding.EINVAL
+    assert L.laa_pool_create(1 << 21, 0, C.byref(base), None, None) == binding.EINVAL
+    assert L.laa_pool_create(1 << 21, 1 << 21, None, None, None) == binding.EINVAL
+    assert L.laa_pool_trim(None, 0, None, None) == binding.EINVAL
+    assert L.laa_pool_trim(C.c_void_p(1 << 21), 0, None, None) == binding.EINVAL       # not a pool
+    assert L.laa_pool_free(None) == binding.OK
+    assert L.laa_pool_free(C.c_void_p(1 << 21)) == binding.EINVAL
 
 
 def test_attach_without_gpu_fails_loudly(L):
