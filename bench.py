@@ -363,7 +363,7 @@ def main():
             tt0 = t - n_it + 1
             pl = sorted(m for i, m in enumerate(ms) if (tt0 + i) % H != 0 and not (lazy and (tt0 + i - 1) % H == 0)) or sorted(ms)
             hist.append(pl[len(pl) // 2])
-            if ref is not None and len(hist) >= 2 and max(hist[-2:]) <= ref * 1.004:      # two windows in a row at the tuner's figure
+            if ref is not None and len(hist) >= 2 and max(hist[-2:]) <= ref * 1.002:      # two windows in a row at the tuner's figure
                 break
             if ref is None and len(hist) >= 4 and max(hist[-3:]) < min(hist[-3:]) * 1.0005:
                 break

@@ -209,6 +209,16 @@ __device__ __forceinline__ Pack<VEC> gradient(const StepArgs &a, int64_t jb, uin
     return g;
 }
 
+// sum / W.  For W a power of two the product with 1/W is the same correctly rounded value as the quotient (scaling by a
+// power of two is exact, and rounds identically when the result is subnormal), so the IEEE division's ten or so
+// instructions per element are spent only for the other W.  The choice is uniform over the grid.
+struct MeanOf {
+    float w, inv;
+    bool pow2;
+    __device__ __forceinline__ explicit MeanOf(int32_t W) : w((float)W), inv(1.0f / (float)W), pow2((W & (W - 1)) == 0) {}
+    __device__ __forceinline__ float operator()(float sum) const { return pow2 ? sum * inv : sum / w; }
+};
+
 // balanced tree over the WT packs of one batch; batches are added in ascending order
 template <int VEC, int WT> __device__ __forceinline__ Pack<VEC> tree_sum(const Pack<VEC> (&v)[WT])
 {
@@ -291,9 +301,9 @@ __device__ __forceinline__ void step_body(const StepArgs &a, const int64_t jb, c
         }
     }
     if constexpr (SYNC && !GRAD_ONLY) {
-        const float fw = (float)a.W;
+        const MeanOf mean(a.W);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
+        for (int e = 0; e < VEC; ++e) { sx.v[e] = mean(sx.v[e]); sb.v[e] = mean(sb.v[e]); }
         if constexpr (COUT) {
             st<VEC, false>(a.x + jb, jl, sx);
         } else {
@@ -381,12 +391,12 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
             for (int e = 0; e < VEC; ++e) sx.v[e] += t.v[e];
         }
     }
-    const float fw = (float)a.W;
+    const MeanOf mean(a.W);
     if constexpr (ALGO == ALGO_DIST_ADAGRAD) {
         Pack<VEC> b2 = ld<VEC, false>(a.snap + jb, jl);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            const float g = sg.v[e] / fw;
+            const float g = mean(sg.v[e]);
             b2.v[e] = fmaf(g, g, b2.v[e]);
             x0.v[e] = x0.v[e] - (a.eta * g) / sqrtf(b2.v[e] + a.eps2);
         }
@@ -401,7 +411,7 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
         st<VEC, false>(a.snap + jb, jl, b2);
     } else if constexpr (SYNC) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) sx.v[e] = sx.v[e] / fw;
+        for (int e = 0; e < VEC; ++e) sx.v[e] = mean(sx.v[e]);
         for (int32_t w = 0; w < a.W; ++w) st<VEC, NT_ST>(a.x + ((int64_t)w * a.pitch + jb), jl, sx);
     }
 }
@@ -439,9 +449,9 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
             for (int e = 0; e < VEC; ++e) sb.v[e] += tb.v[e];
         }
     }
-    const float fw = (float)W;
+    const MeanOf mean(W);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { sx.v[e] = sx.v[e] / fw; sb.v[e] = sb.v[e] / fw; }
+    for (int e = 0; e < VEC; ++e) { sx.v[e] = mean(sx.v[e]); sb.v[e] = mean(sb.v[e]); }
     if constexpr (COUT) {
         st<VEC, false>(x + jb, jl, sx);
     } else {

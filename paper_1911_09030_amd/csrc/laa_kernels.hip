@@ -348,7 +348,7 @@ __global__ __launch_bounds__(WAVE) void mean_rows_kernel(float *__restrict__ x, 
     uint64_t it = blockIdx.x;
     if (it >= items) return;
     const int lane = threadIdx.x;
-    const float fw = (float)W;
+    const MeanOf mean(W);
     int32_t row = list[it / chunks];
     while (true) {
         const uint64_t nxt = it + gridDim.x;
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(WAVE) void mean_rows_kernel(float *__restrict__ x, 
                 for (int c = 0; c < 4; ++c) { sx.v[c] += tx.v[c]; sb.v[c] += tb.v[c]; }
             }
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { sx.v[c] = sx.v[c] / fw; sb.v[c] = sb.v[c] / fw; }
+            for (int c = 0; c < 4; ++c) { sx.v[c] = mean(sx.v[c]); sb.v[c] = mean(sb.v[c]); }
             for (int32_t w = 0; w < W; ++w) {
                 st<4, ROWS_NT>(x + (int64_t)w * pitch + col, sx);
                 st<4, ROWS_NT>(acc + (int64_t)w * pitch + col, sb);

@@ -66,9 +66,10 @@ def candidates(pool_elems, d, W, n_matrices, n_vectors, n_random, seed):
     return out
 
 
-def tune(pool, d, W, n_matrices, n_vectors, measure, n_random=48, seed=0, confirm=3, log=None):
+def tune(pool, d, W, n_matrices, n_vectors, measure, n_random=48, seed=0, confirm=3, refine=6, log=None):
     """Time measure(matrices, vectors, pitch) -> milliseconds on candidate placements inside `pool` and return the
-    fastest Layout (its three best are timed a second time and the best of those wins).  `matrices` are [W][d]
+    fastest Layout: first the candidates, then `refine` variations of each of the best four (one array group moved
+    elsewhere); the three best are timed a second time and the best of those wins.  `matrices` are [W][d]
     float32 views with row pitch `pitch`, `vectors` are [d] views; measure must leave nothing running."""
     pool_elems = pool.nbytes // 4
     tried = []
@@ -79,6 +80,26 @@ def tune(pool, d, W, n_matrices, n_vectors, measure, n_random=48, seed=0, confir
             log(f"placement pitch {lay.pitch} matrices {lay.matrices} vectors {lay.vectors[0]}: {lay.ms:.4f} ms")
     if not tried:
         raise ValueError("the pool is too small for the arrays")
+    tried.sort(key=lambda l: l.ms)
+    # second stage: around the best few, move one part of the placement (a matrix or the block of vectors) elsewhere
+    rng = random.Random(seed + 1)
+    dp = _round_up(d)
+    for parent in list(tried[:4]):
+        for _ in range(refine):
+            mats, vb = list(parent.matrices), parent.vectors[0]
+            k = rng.randrange(len(mats) + 1)
+            if k < len(mats):
+                mats[k] = _round_up(rng.randrange(0, max(pool_elems - W * parent.pitch, 1)))
+            else:
+                vb = _round_up(rng.randrange(0, max(pool_elems - n_vectors * dp, 1)))
+            spans = [(m, m + (W - 1) * parent.pitch + d) for m in mats] + [(vb, vb + (n_vectors - 1) * dp + d)]
+            if max(e for _, e in spans) > pool_elems or not _disjoint(spans):
+                continue
+            lay = Layout(parent.pitch, mats, [vb + v * dp for v in range(n_vectors)])
+            lay.ms = _run(pool, d, W, lay, measure)
+            tried.append(lay)
+            if log:
+                log(f"placement (refined) pitch {lay.pitch} matrices {lay.matrices} vectors {lay.vectors[0]}: {lay.ms:.4f} ms")
     tried.sort(key=lambda l: l.ms)
     best = tried[0]
     for lay in tried[:confirm]:

@@ -227,8 +227,8 @@ def test_pool_and_measured_placement(B):
         timed.append(m)
         return m
 
-    best = placement.tune(pool, d, W, 2, 3, measure, n_random=6, seed=1)
-    assert best.tried == len(timed) - 3 and best.ms > 0 and best.pitch >= d and best.pitch % 1024 == 0
+    best = placement.tune(pool, d, W, 2, 3, measure, n_random=6, seed=1, refine=2)
+    assert best.tried == len(timed) - 3 and best.tried > 16 + 6 and best.ms > 0 and best.pitch >= d and best.pitch % 1024 == 0
     spans = sorted(best.ranges(d, W))
     assert all(a + n <= b for (a, n), (b, _) in zip(spans, spans[1:])), "arrays overlap"
     (x, acc), (snap, a, xs) = placement.views(pool, d, W, best)
@@ -1136,7 +1136,7 @@ def _quadratic_setup(B, c, n_groups, off_mode="philox", bench_layout=False):
         from paper_1911_09030_amd import placement
         pool = B.Pool(int(torch.cuda.mem_get_info()[0] * 0.9))
         measure = placement.quadratic_step_timer(c.d, c.W, c.eta, c.eps, c.seed, om, c.noise_scale, c.off_scale)
-        best = placement.tune(pool, c.d, c.W, 2, 3, measure, n_random=8, seed=c.seed)
+        best = placement.tune(pool, c.d, c.W, 2, 3, measure, n_random=8, seed=c.seed, refine=1)
         (bx, bacc), (bsnap, da, dxs) = placement.views(pool, c.d, c.W, best)
         pool.trim(best.ranges(c.d, c.W))
         say(f"   placement: {best.tried} timed, best {best.ms:.3f} ms, slowest {best.slowest_ms:.3f} ms")
