@@ -571,6 +571,32 @@ def test_generator_gradient_and_fused_step(B, mode, off_mode, W, d, tile):
         parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, bar, floor_x=1.0, what=f"gen t={t}")
 
 
+@pytest.mark.parametrize("noise_scale,off_scale", [(0.0, 0.1), (0.1, 0.0), (0.0, 0.0), (2.5, 0.01), (1e-3, 3.0)])
+def test_generator_scales(B, noise_scale, off_scale):
+    """Standard deviations of the noise and of the per-worker offsets away from the workloads' 0.1, zero included
+    (a zero scale must switch its term off exactly: the kernels fold the scale into the Box-Muller radius)."""
+    import torch
+    W, H, d = 4, 3, 4 * 64 * 5 + 8
+    rng = np.random.default_rng(29)
+    a = rng.uniform(0.1, 10, d).astype(np.float32); xs = rng.standard_normal(d).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    o = Oracle(d, W, H, 0.05, 1.0); o.init_state(x0)
+    o.set_generator(oracle.GEN_QUADRATIC, 11, a, xs, None, oracle.OFF_PHILOX, noise_scale, off_scale)
+    g = B.LocalAdaAlter(d, W, H, 0.05, 1.0); g.init_state(dev(x0))
+    g.set_generator(B.GEN_QUADRATIC, 11, dev(a), dev(xs), None, B.OFF_PHILOX, noise_scale, off_scale)
+    for t in range(1, 2 * H + 1):
+        G_ref, G_gpu = o.gradient(t), host(g.generate_gradient())
+        S = _gen_scale(a, o.x, xs, off_scale, noise_scale)
+        assert np.max(np.abs(G_gpu - G_ref) / np.maximum(S, 1e-30)) <= 1e-6, t
+        if noise_scale == 0.0 and off_scale == 0.0:        # nothing random left: every worker sees a (x - xstar)
+            assert np.array_equal(G_gpu, (a[None, :] * (host(g.x) - xs[None, :])).astype(np.float32))
+        o.step_gen(); g.step_gen()
+    parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, 1e-5, floor_x=1.0, what="generator scales")
+    with pytest.raises(B.LaaError) as ei:
+        g.set_generator(B.GEN_QUADRATIC, 11, dev(a), dev(xs), None, B.OFF_PHILOX, -0.1, 0.1)
+    assert ei.value.code == B.EINVAL
+
+
 @pytest.mark.parametrize("d,split", [(4 * 64 * 11, 4 * 64 * 4), (4 * 300 + 2, 4 * 77)])
 def test_shard_by_columns_equals_the_unsplit_run(B, d, split):
     """Two handles that hold columns [0, split) and [split, d) with laa_set_shard reproduce the unsplit run bit for
