@@ -463,8 +463,13 @@ __device__ __forceinline__ void mean_body(float *__restrict__ x, float *__restri
     if constexpr (!X_ONLY) st<VEC, false>(snap + jb, jl, sb);
 }
 
+// At most 2 wavefronts per SIMD for the averaging kernels too (2W loads in flight per lane): the whole-table mean of a
+// 409.6M-column table ran in 8.38 ms with 2, 8.48 with 3, 8.58 with 4, 8.45-8.54 uncapped (7).
+#ifndef LAA_MEAN_WAVES
+#define LAA_MEAN_WAVES 2
+#endif
 template <int VEC, int WT, bool X_ONLY, bool COUT>
-__global__ __launch_bounds__(DBLOCK) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
+__global__ __launch_bounds__(DBLOCK) __attribute__((amdgpu_waves_per_eu(1, LAA_MEAN_WAVES))) void mean_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                      float *__restrict__ snap, int64_t d, int64_t pitch, int32_t W)
 {
     int64_t jb;

@@ -58,7 +58,8 @@ __global__ __launch_bounds__(BLOCK) void copy_kernel(v4f *__restrict__ dst, cons
 // sync averages only rows some worker changed.
 static constexpr int WAVE = 64;
 static constexpr int WAVES_PER_BLOCK = BLOCK / WAVE;
-
+// (64-thread blocks: the same 0.129 ms on the embedding workload; non-temporal accesses to x and acc: 0.137-0.147 ms,
+// the frequent rows are served from the caches.)
 __global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
 {
     const int64_t pair = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x / WAVE);
@@ -322,11 +323,12 @@ __global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__re
 // grid of one-wavefront blocks strides over the work items, an item being 256 consecutive floats of a listed row
 // (16 bytes per lane) for all W workers: 2W non-temporal 16-byte loads in flight per lane, 2W + 1 stores.  The row
 // number of the next item is fetched before the current item's loads are waited for.  Measured on the embedding
-// workload (290 000 of 800 000 rows of 512 floats listed, W = 8): 3.20 ms with 32 such blocks per CU, 3.26 with 16 or
-// 8, 3.35 with cached instead of non-temporal accesses, 3.33 with one block per item under a grid that covers the
-// largest possible list (most of its blocks leave at once).
+// workload (290 000 of 800 000 rows of 512 floats listed, W = 8; list compaction included): 3.14 ms with 2 wavefronts
+// per SIMD (8 blocks per CU), 3.18 with 3, 3.23 with 4, 3.17-3.21 uncapped with 32 blocks per CU; 3.35 with cached
+// instead of non-temporal accesses, 3.33 with one block per item under a grid that covers the largest possible list
+// (most of its blocks leave at once).
 #ifndef LAA_ROWS_WAVES_PER_CU
-#define LAA_ROWS_WAVES_PER_CU 32
+#define LAA_ROWS_WAVES_PER_CU 8
 #endif
 #ifndef LAA_ROWS_NT
 #define LAA_ROWS_NT true
@@ -334,8 +336,11 @@ __global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__re
 static constexpr int N_CU = 256;                                     // MI355X
 static constexpr bool ROWS_NT = LAA_ROWS_NT;
 
+#ifndef LAA_ROWS_WAVES
+#define LAA_ROWS_WAVES 2               // wavefronts per SIMD; the grid holds exactly that many per CU
+#endif
 template <int WT>
-__global__ __launch_bounds__(WAVE) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
+__global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(1, LAA_ROWS_WAVES))) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                          float *__restrict__ snap, int64_t pitch, int32_t W,
                                                          int32_t row_len, const int32_t *__restrict__ list,
                                                          const uint32_t *__restrict__ count,
