@@ -186,10 +186,10 @@ def spread_arrays(d, W, n_matrices, n_vectors, row_distance, device="cuda:0", ho
     Returns (backing, matrices, vectors, pitch); every matrix has row pitch ``pitch``; keep ``backing`` alive as
     long as the tensors are used.
 
-    Why: on MI355X a thread's 2W read-modify-write streams run 6-8 % faster when the arrays streamed together
+    Why: on MI355X a thread's 2W read-modify-write streams mostly run faster when the arrays streamed together
     span most of the HBM address range (d = 4e8, W = 8: 8.7-8.9 ms per step with the arrays 10 GB apart against
-    9.1-9.5 ms when packed into 30 GB; the threshold scales as 1/(number of streams), as if a third of the
-    address range maps to one rank of the 12-high stacks).
+    8.8-9.8 ms for ordinary packed tensors).  placement.tune over a Pool finds a good placement by measurement
+    instead (8.7 ms), which is what bench.py uses.
 
     Default: laa_spread_alloc, which maps only the arrays themselves (the address range between them is
     reserved but unmapped, so it costs no device memory; never touch it).  hold_gaps=True: one ordinary
