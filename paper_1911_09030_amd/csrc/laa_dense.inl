@@ -416,8 +416,18 @@ __device__ __forceinline__ void baseline_body(const StepArgs &a, const int64_t j
     }
 }
 
+// Wavefronts per SIMD of the two comparison algorithms, measured at d = 4e8, W = 8 with the generated gradient: Local SGD
+// 4.53 ms with 2, 4.75 with 3, 4.84 with 4, 5.08 uncapped (7); Distributed AdaGrad on W replicas 6.83 with 2, 6.86 with 3,
+// 6.87 uncapped. The single-iterate AdaGrad step is bound by the generator's arithmetic and wants every wavefront it
+// can get (3.09-3.12 ms uncapped, 3.24 with 2).
+#ifndef LAA_BASELINE_WAVES
+#define LAA_BASELINE_WAVES 2
+#endif
+static constexpr int baseline_waves(bool row0) { return row0 ? 8 : LAA_BASELINE_WAVES; }
+
 template <int VEC, int WT, int GS, int OS, int ALGO, bool SYNC, bool ROW0 = false>
-__global__ __launch_bounds__(DBLOCK) void baseline_kernel(const StepArgs a)
+__global__ __launch_bounds__(DBLOCK) __attribute__((amdgpu_waves_per_eu(1, baseline_waves(ROW0))))
+void baseline_kernel(const StepArgs a)
 {
     int64_t jb;
     uint32_t jl;
