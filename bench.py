@@ -32,6 +32,9 @@ def parse():
     p.add_argument("--warmup", type=int, default=16)
     p.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     p.add_argument("--H", type=int, default=0, help="override the sync period (c3 sweep)")
+    p.add_argument("--algorithm", default="local_adaalter", choices=["local_adaalter", "dist_adagrad", "local_sgd"],
+                   help="quadratic workloads: Algorithm 3 (the method), or one of the paper's two comparison methods on the same "
+                        "inputs: Algorithm 1 (averages every iteration, H is ignored) or Algorithm 2 (no accumulator)")
     p.add_argument("--offsets", default="philox", choices=["philox", "array", "none"],
                    help="per-worker optimum offsets: regenerated in-kernel, read from HBM, or absent")
     p.add_argument("--row-distance", type=int, default=0,
@@ -162,6 +165,12 @@ def main():
             sys.exit(2)
         torch.cuda.set_stream(torch.cuda.Stream(device=dev))     # the default stream cannot be captured
     H = args.H or c.H
+    algo = args.algorithm
+    if algo != "local_adaalter" and (c.kind != "quadratic" or args.graph or args.unfused_sync):
+        print("bench.py: --algorithm runs the fused generator step of the quadratic workloads (c1, c2, c5)", file=sys.stderr)
+        sys.exit(2)
+    if algo == "dist_adagrad":
+        H = 1
     K, Wm = (args.steps if args.steps is not None else c.T), args.warmup
     d, W = c.d, c.W
 
@@ -214,9 +223,14 @@ def main():
         om = {"philox": B.OFF_PHILOX, "array": B.OFF_ARRAY, "none": B.OFF_NONE}[args.offsets]
 
         from paper_1911_09030_amd import placement
-        measure = placement.quadratic_step_timer(d, W, c.eta, c.eps, c.seed, om, c.noise_scale, c.off_scale, args.tile)
+        algo_id = {"local_adaalter": None, "dist_adagrad": B.ALGO_DIST_ADAGRAD, "local_sgd": B.ALGO_LOCAL_SGD}[algo]
+        measure = placement.quadratic_step_timer(d, W, c.eta, c.eps, c.seed, om, c.noise_scale, c.off_scale, args.tile,
+                                                 algo_id, algo == "dist_adagrad" and not args.no_lazy_replicas)
         mats, (bsnap, a, xs), rp = alloc(d, 3 if with_off else 2, 3, measure)
-        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
+        g = B.LocalAdaAlter(d, W, H, c.eta, c.eps, b0=0.0 if algo == "dist_adagrad" else None,
+                            x=mats[0], acc=mats[1], snap=bsnap, pitch=rp)
+        if algo_id is not None:
+            g.set_algorithm(algo_id)
         a.copy_(torch.from_numpy(wl.curvature(d, c.seed, c.a_dist)))
         xs.copy_(torch.from_numpy(wl.optimum(d, c.seed)))
         g.init_state()
@@ -228,6 +242,14 @@ def main():
         g.set_generator(B.GEN_QUADRATIC, c.seed, a, xs, off, om, c.noise_scale, c.off_scale)
         step_bytes = (16 * W + 12 + (4 * W if off is not None else 0)) * d
         kernel_tag = f"step_kernel_{c.name}"
+        if algo != "local_adaalter":
+            # Algorithm 1 reads every x row, a, x* and snap and writes every x and acc row and snap (with lazy replicas its
+            # one iterate is row 0 of x and snap); Algorithm 2 reads and writes every x row and reads a, x*.  Every
+            # iteration of Algorithm 1 is the same kernel, and Algorithm 2's averaging moves what its plain step moves.
+            lazy_on = not args.no_lazy_replicas
+            per_col = ((24 if lazy_on else 12 * W + 16) if algo == "dist_adagrad" else 8 * W + 8) + (4 * W if off is not None else 0)
+            step_bytes = per_col * d
+            kernel_tag = f"baseline_kernel_{algo}_{c.name}"
         if args.unfused_sync:
             def do_step(t):
                 g.local_step_gen()
@@ -312,7 +334,7 @@ def main():
         updates_per_step = W * c.k * c.row_len + W * dd
     if args.tile is not None:
         g.set_tile(args.tile)
-    lazy = not args.no_lazy_replicas and c.kind != "embedding"
+    lazy = not args.no_lazy_replicas and c.kind != "embedding" and algo != "local_sgd"    # Algorithm 2 has no collapsed state
     if lazy:
         g.set_lazy_replicas(True)
     if not args.no_lazy_replicas and c.kind == "embedding":
@@ -412,7 +434,10 @@ def main():
         # iteration tt averages when tt % H == 0 and, with lazy replicas, reads a collapsed state when the one before it averaged
         for i in range(K):
             tt = t_first + i
-            kinds.append("sync" if tt % H == 0 else "post" if lazy and tt > 1 and (tt - 1) % H == 0 else "plain")
+            if algo == "dist_adagrad":       # one kernel, every iteration
+                kinds.append("plain")
+            else:
+                kinds.append("sync" if tt % H == 0 else "post" if lazy and tt > 1 and (tt - 1) % H == 0 else "plain")
         align()
     n_timed = reps * K
     if args.graph:
@@ -464,7 +489,10 @@ def main():
     # one whole period in the steady state, from the per-kind iteration times: independent of how many iterations of
     # each kind the timed region happened to hold
     steady_ms = steady_value = None
-    if not args.graph and c.kind != "embedding":
+    if algo == "dist_adagrad":
+        steady_ms = mean_of(by_kind["plain"])
+        steady_value = updates_per_step / (steady_ms * 1e-3)
+    elif not args.graph and c.kind != "embedding":
         n_post = 1 if (lazy and H >= 2) else 0
         parts = [(H - 1 - n_post, mean_of(by_kind["plain"])), (1, ms_sync), (n_post, ms_post)]
         if all(n == 0 or m is not None for n, m in parts):
@@ -495,7 +523,7 @@ def main():
     # benchmark's choice of placement; a caller with plain allocations gets this figure).
     packed = None
     if (c.kind == "quadratic" and spread and layouts and not layouts[0].startswith("packed") and not args.graph
-            and not args.no_packed_compare and not args.unfused_sync and args.offsets != "array"):
+            and not args.no_packed_compare and not args.unfused_sync and args.offsets != "array" and algo == "local_adaalter"):
         pa, pxs = a.clone(), xs.clone()
         gp = B.LocalAdaAlter(d, W, H, c.eta, c.eps)
         gp.init_state()
@@ -529,7 +557,7 @@ def main():
         "value": value, "unit": "element-updates/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": updates_per_step / value * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{c.name}: d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
+        "config": {"workload": f"{c.name}: {'' if algo == 'local_adaalter' else 'algorithm=' + algo + ' '}d={d} W={W} H={H} eta={c.eta} eps={c.eps} kind={c.kind} "
                                f"offsets={args.offsets if c.kind == 'quadratic' else 'n/a'} "
                                f"sync={'separate kernel' if args.unfused_sync else 'fused into the H-th step'} "
                                f"lazy_replicas={'on' if lazy else 'off'} layout={'+'.join(layouts)}"
@@ -551,7 +579,7 @@ def main():
                      "kernel_ms_median": statistics.median(plain), "kernel_ms_max": max(plain), "kernel_launches_timed": len(plain),
                      "algorithmic_bytes_per_launch": step_bytes, "copy_kernel_gbs_same_run": copy_gbs},
     }
-    if not args.no_cpu_baseline and c.kind == "quadratic":
+    if not args.no_cpu_baseline and c.kind == "quadratic" and algo == "local_adaalter":
         out["cpu_baseline"] = cpu_baseline(c, min(args.cpu_sample_d, d), args.offsets, args.cpu_procs, args.cpu_reps)
     print(json.dumps(out), flush=True)
 

@@ -134,10 +134,13 @@ def event_median_ms(step, n=5):
     return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
 
 
-def generator_step_timer(d, W, eta, eps, seed, mode, off_mode, noise_scale, off_scale, tile=None):
+def generator_step_timer(d, W, eta, eps, seed, mode, off_mode, noise_scale, off_scale, tile=None, algorithm=None,
+                         lazy=False):
     """measure() for tune(): the plain generator step (no averaging in reach) on arrays at a candidate placement.
     Quadratic mode: matrices (x, acc[, stored offsets]), vectors (snap, a, xstar); noise mode: matrices (x, acc),
-    vectors (snap, a).  The inputs are constants: the step's duration does not depend on their values."""
+    vectors (snap, a).  The inputs are constants: the step's duration does not depend on their values.
+    `algorithm` (a binding.ALGO_* value) times the step of that algorithm instead of Local AdaAlter's; `lazy` switches
+    lazy replicas on (it changes the kernel of Distributed AdaGrad, whose every step averages)."""
     from . import binding as B
 
     def measure(mats, vecs, pitch):
@@ -151,6 +154,10 @@ def generator_step_timer(d, W, eta, eps, seed, mode, off_mode, noise_scale, off_
             off = mats[2]
             off.zero_()
         h = B.LocalAdaAlter(d, W, 1 << 30, eta, eps, x=mats[0], acc=mats[1], snap=vecs[0], pitch=pitch)
+        if algorithm is not None:
+            h.set_algorithm(algorithm)
+        if lazy:
+            h.set_lazy_replicas(True)
         h.init_state()
         h.set_generator(mode, seed, vecs[1], xstar, off, off_mode, noise_scale, off_scale)
         if tile is not None:
@@ -163,9 +170,9 @@ def generator_step_timer(d, W, eta, eps, seed, mode, off_mode, noise_scale, off_
     return measure
 
 
-def quadratic_step_timer(d, W, eta, eps, seed, off_mode, noise_scale, off_scale, tile=None):
+def quadratic_step_timer(d, W, eta, eps, seed, off_mode, noise_scale, off_scale, tile=None, algorithm=None, lazy=False):
     from . import binding as B
-    return generator_step_timer(d, W, eta, eps, seed, B.GEN_QUADRATIC, off_mode, noise_scale, off_scale, tile)
+    return generator_step_timer(d, W, eta, eps, seed, B.GEN_QUADRATIC, off_mode, noise_scale, off_scale, tile, algorithm, lazy)
 
 
 def averaging_timer(d, W, eta, eps):
