@@ -406,7 +406,10 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-template <int VEC, int OS>
+// WT > 0: the table has exactly WT workers and a thread keeps their WT column groups in registers, so every row of x
+// is read once (streaming loads); WT == 0: any W, the rows are read a second time for the deviations.  Both add in
+// the same order.
+template <int VEC, int OS, int WT>
 __global__ __launch_bounds__(BLOCK) void diag_kernel(const StepArgs a, double *__restrict__ partial)
 {
     double s0 = 0.0, s1 = 0.0, s2 = 0.0;
@@ -414,34 +417,53 @@ __global__ __launch_bounds__(BLOCK) void diag_kernel(const StepArgs a, double *_
     const float fw = (float)a.W;
     for (int64_t q = (int64_t)blockIdx.x * BLOCK + threadIdx.x; q < n_groups; q += (int64_t)gridDim.x * BLOCK) {
         const int64_t j = q * VEC;
-        const Pack<VEC> av = ld<VEC, false>(a.a + j), xs = ld<VEC, false>(a.xstar + j);
+        const Pack<VEC> av = ld<VEC, true>(a.a + j), xs = ld<VEC, true>(a.xstar + j);
         Pack<VEC> xbar, moff, dev;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) xbar.v[e] = moff.v[e] = dev.v[e] = 0.0f;
-        const int32_t rows = a.collapsed_in ? 1 : a.W;
-        for (int32_t w = 0; w < rows; ++w) {
-            const Pack<VEC> xv = ld<VEC, false>(a.x + (int64_t)w * a.pitch + j);
+        if (a.collapsed_in) {                 // every worker holds row 0: the mean is that row, the deviations are zero
+            xbar = ld<VEC, true>(a.x + j);
+        } else if constexpr (WT > 0) {
+            Pack<VEC> xv[WT];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) xbar.v[e] += xv.v[e];
-        }
+            for (int w = 0; w < WT; ++w) xv[w] = ld<VEC, true>(a.x + (int64_t)w * a.pitch + j);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) xbar.v[e] = xbar.v[e] / (float)rows;
-        for (int32_t w = 0; w < a.W; ++w) {
-            if (!a.collapsed_in) {
+            for (int w = 0; w < WT; ++w)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) xbar.v[e] += xv[w].v[e];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) xbar.v[e] = xbar.v[e] / fw;
+#pragma unroll
+            for (int w = 0; w < WT; ++w)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { const float t = xv[w].v[e] - xbar.v[e]; dev.v[e] = fmaf(t, t, dev.v[e]); }
+        } else {
+            for (int32_t w = 0; w < a.W; ++w) {
+                const Pack<VEC> xv = ld<VEC, false>(a.x + (int64_t)w * a.pitch + j);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) xbar.v[e] += xv.v[e];
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) xbar.v[e] = xbar.v[e] / fw;
+            for (int32_t w = 0; w < a.W; ++w) {
                 const Pack<VEC> xv = ld<VEC, false>(a.x + (int64_t)w * a.pitch + j);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) { const float t = xv.v[e] - xbar.v[e]; dev.v[e] = fmaf(t, t, dev.v[e]); }
             }
-            if constexpr (OS == OFFSET_ARRAY) {
-                const Pack<VEC> o = ld<VEC, false>(a.off + (int64_t)w * a.pitch + j);
+        }
+        if constexpr (OS != OFFSET_NONE) {
+            for (int32_t w = 0; w < a.W; ++w) {
+                if constexpr (OS == OFFSET_ARRAY) {
+                    const Pack<VEC> o = ld<VEC, true>(a.off + (int64_t)w * a.pitch + j);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) moff.v[e] += o.v[e];
-            } else if constexpr (OS == OFFSET_PHILOX) {
-                const uint64_t ja = (uint64_t)(j + a.col0);
-                const Normals4 m = normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, ja >> 2, (uint32_t)(w + a.w0), 0u, a.off_c);
-                const int lane0 = VEC == 4 ? 0 : (int)(ja & 3);
+                    for (int e = 0; e < VEC; ++e) moff.v[e] += o.v[e];
+                } else {
+                    const uint64_t ja = (uint64_t)(j + a.col0);
+                    const Normals4 m = normals4(a.seed_lo, a.seed_hi, STREAM_OFFSET, ja >> 2, (uint32_t)(w + a.w0), 0u, a.off_c);
+                    const int lane0 = VEC == 4 ? 0 : (int)(ja & 3);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) moff.v[e] += m.rad[(lane0 + e) >> 1] * m.trig[lane0 + e];
+                    for (int e = 0; e < VEC; ++e) moff.v[e] += m.rad[(lane0 + e) >> 1] * m.trig[lane0 + e];
+                }
             }
         }
 #pragma unroll
@@ -465,14 +487,16 @@ __global__ __launch_bounds__(BLOCK) void diag_kernel(const StepArgs a, double *_
     }
 }
 
-__global__ __launch_bounds__(WAVE) void diag_final_kernel(const double *__restrict__ partial, int32_t n_blocks,
-                                                         double *__restrict__ out)
+// One wavefront per quantity: lane l adds the partials of blocks l, l + 64, ... in that order, then the lanes are
+// added by the same shuffle tree as above: a fixed order again.
+__global__ __launch_bounds__(3 * WAVE) void diag_final_kernel(const double *__restrict__ partial, int32_t n_blocks,
+                                                             double *__restrict__ out)
 {
-    if (threadIdx.x < 3) {
-        double t = 0.0;
-        for (int32_t b = 0; b < n_blocks; ++b) t += partial[(int64_t)b * 3 + threadIdx.x];
-        out[threadIdx.x] = t;
-    }
+    const int lane = threadIdx.x % WAVE, k = threadIdx.x / WAVE;
+    double t = 0.0;
+    for (int32_t b = lane; b < n_blocks; b += WAVE) t += partial[(int64_t)b * 3 + k];
+    t = wave_sum(t);
+    if (lane == 0) out[k] = t;
 }
 
 __global__ void philox_debug_kernel(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
@@ -576,7 +600,14 @@ hipError_t launch_diagnostics(const StepArgs &a_in, double *scratch, hipStream_t
     const int32_t nb = (int32_t)(want < DIAG_BLOCKS ? want : DIAG_BLOCKS);
     double *out = scratch + DIAG_BLOCKS * 3;
     const dim3 grid((unsigned)nb), block(BLOCK);
-#define LAA_DIAG(VEC, OS) hipLaunchKernelGGL((diag_kernel<VEC, OS>), grid, block, 0, s, a, scratch)
+#define LAA_DIAG_W(VEC, OS, WT) hipLaunchKernelGGL((diag_kernel<VEC, OS, WT>), grid, block, 0, s, a, scratch)
+#define LAA_DIAG(VEC, OS)                                      \
+    do {                                                       \
+        if (a.W == 8) LAA_DIAG_W(VEC, OS, 8);                  \
+        else if (a.W == 4) LAA_DIAG_W(VEC, OS, 4);             \
+        else if (a.W == 2) LAA_DIAG_W(VEC, OS, 2);             \
+        else LAA_DIAG_W(VEC, OS, 0);                           \
+    } while (0)
     if (a.vec4) {
         if (a.d % 4 != 0) return hipErrorInvalidValue;
         if (a.off_source == OFFSET_ARRAY) LAA_DIAG(4, OFFSET_ARRAY);
@@ -587,8 +618,9 @@ hipError_t launch_diagnostics(const StepArgs &a_in, double *scratch, hipStream_t
         else if (a.off_source == OFFSET_PHILOX) LAA_DIAG(1, OFFSET_PHILOX);
         else LAA_DIAG(1, OFFSET_NONE);
     }
+#undef LAA_DIAG_W
 #undef LAA_DIAG
-    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(WAVE), 0, s, scratch, nb, out);
+    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(3 * WAVE), 0, s, scratch, nb, out);
     return hipGetLastError();
 }
 
