@@ -1267,6 +1267,56 @@ def test_config5_full_length_on_sampled_columns(B):
     torch.cuda.empty_cache()
 
 
+def test_config5_size_adagrad_and_local_sgd_on_sampled_columns(B):
+    """Algorithms 1 and 2 on the headline workload's inputs at its full size (d = 4e8, W = 8): the kernels that
+    `bench.py --algorithm` times, with 64-bit column offsets in reach.  The oracle follows 2048 sampled columns (the
+    last column group among them): its gradient at every iteration, then its Algorithm 1 / Algorithm 2 step."""
+    import torch
+    c = wl.WORKLOADS["c5"]
+    cols = wl.column_sample(c.d, 512, seed=2)
+    a, xs = wl.curvature(c.d, c.seed, c.a_dist), wl.optimum(c.d, c.seed)
+    da, dxs = dev(a), dev(xs)
+    sa, sxs = a[cols], xs[cols]
+    del a, xs
+    x = torch.empty((c.W, c.d), dtype=torch.float32, device="cuda:0")
+    acc = torch.empty_like(x)
+    snap = torch.empty(c.d, dtype=torch.float32, device="cuda:0")
+    for algo, lazy in (("adagrad", False), ("adagrad", True), ("sgd", False)):
+        say(f"   {algo} lazy={lazy} at d={c.d}")
+        H, T, b0 = (1, 5, 0.0) if algo == "adagrad" else (c.H, c.H + 2, 1.0)
+        o = Oracle(len(cols), c.W, H, c.eta, c.eps, b0)
+        o.set_columns(cols); o.init_state()
+        o.set_generator(oracle.GEN_QUADRATIC, c.seed, sa, sxs, None, oracle.OFF_PHILOX, c.noise_scale, c.off_scale)
+        g = B.LocalAdaAlter(c.d, c.W, H, c.eta, c.eps, b0=b0, x=x, acc=acc, snap=snap)
+        g.set_algorithm(B.ALGO_DIST_ADAGRAD if algo == "adagrad" else B.ALGO_LOCAL_SGD)
+        g.set_lazy_replicas(lazy)
+        g.init_state()
+        g.set_generator(B.GEN_QUADRATIC, c.seed, da, dxs, None, B.OFF_PHILOX, c.noise_scale, c.off_scale)
+        sc = parity.Scale(o)
+        S2 = np.zeros(len(cols))
+        for t in range(1, T + 1):
+            S = _gen_scale(sa, o.x, sxs, c.off_scale, c.noise_scale)
+            np.maximum(S2, np.max(S * np.ones((c.W, 1)), axis=0) ** 2, out=S2)
+            G_ref = o.gradient(t)
+            (o.adagrad_step_dense if algo == "adagrad" else o.localsgd_step_dense)(G_ref)
+            g.step_gen(); sc.update(o)
+        if algo == "adagrad" and lazy:
+            g.materialize()
+        ex = parity.rel_err(_sampled(g.x, cols), o.x, 1.0, sc.s)
+        say(f"   {algo} lazy={lazy}: rel err x {ex:.2e}")
+        assert ex <= 1e-5, f"{algo} lazy={lazy}: x {ex:.2e}"
+        if algo == "adagrad":
+            es = parity.rel_err(_sampled(g.snap, cols), o.snap, 1e-3, S2)
+            assert es <= 1e-5, f"adagrad lazy={lazy}: B2 {es:.2e}"
+            assert torch.equal(g.x[0], g.x[c.W - 1]) and torch.equal(g.acc[c.W - 1], g.snap)
+        else:       # T = H + 2: two local steps after the averaging, the workers have moved apart again
+            assert not torch.equal(g.x[0], g.x[c.W - 1])
+        assert g.counters()[0] == T
+        g.close()
+    del x, acc, snap, da, dxs
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("H,T", [(1, 64), (4, 128), (16, 512), (64, 128)])
 def test_config3_explicit_gradient_pool(B, H, T):
     """d=100M, W=8: dense gradients N(0, sigma_j^2) precomputed into HBM, streamed by the explicit-gradient step; the
