@@ -17,7 +17,8 @@
  *   - "device" pointers are HIP device memory owned by the CALLER (allocated
  *     e.g. through PyTorch).  The library allocates only small bookkeeping
  *     buffers of its own, on first use (the dirty-row bitmap of the sparse
- *     steps; the row list of laa_sync after sparse steps and of
+ *     steps and, for W <= 64, 8 bytes per table row naming the workers that
+ *     stepped it; the row list of laa_sync after sparse steps and of
  *     laa_get_dirty_rows; sort keys and partial rows of the coalescing sparse step,
  *     48 KiB of reduction scratch for laa_diagnostics, 8 bytes for
  *     laa_run_periods_gen), freed by laa_destroy.
@@ -196,7 +197,10 @@ int laa_set_sparse_coalesce(laa_handle h, int32_t on);
 
 /* Algorithm 3, Synchronize: x[w] and acc[w] become the means over w, snap the
  * mean acc.  After only sparse steps just the rows touched since the last sync
- * are averaged (all other rows are already equal on every worker).  A call with
+ * are averaged (all other rows are already equal on every worker), and of such
+ * a row only the rows of the workers that stepped it and of one that did not are
+ * read (the others hold the same values; W <= 64): the result is bit for bit
+ * the one that reading every worker's row gives.  A call with
  * no step since the last sync is a no-op; an early call (fewer than H steps) is
  * allowed and restarts t' at 1. */
 int laa_sync(laa_handle h);
@@ -249,12 +253,17 @@ int laa_diagnostics(laa_handle h, double *out);
  *   *moved_bytes:   what the launches read and write: x, acc of every worker and snap once per column, the
  *                   generator's arrays or the explicit gradients, the averaged state; with lazy replicas the
  *                   collapsed state counts as what it is (row 0 of x and snap, 8 bytes per column), and so do
- *                   laa_materialize, the sort keys of the coalescing step and the rows averaged after sparse steps.
+ *                   laa_materialize, the sort keys of the coalescing step and the rows averaged after sparse steps
+ *                   (per averaged row: x and acc rows of the workers that stepped it and of one that did not
+ *                   read, every worker's rows and snap's written).
  *                   Dividing it by the elapsed time gives the rate the memory system delivered.
  *   *literal_bytes: the same iterations as Algorithm 3 spells them out, a local step over full replicas
  *                   (16 W + 4 bytes per column and the gradient's inputs) and a separate Synchronize pass
- *                   (16 W + 4) whenever one averaged: the traffic that fusing and lazy replicas save is still in it.
- * After sparse steps the number of averaged rows is read from the device: the call then synchronises the stream. */
+ *                   (16 W + 4; after sparse steps: that many bytes per element of the averaged rows) whenever
+ *                   one averaged: the traffic that fusing, lazy replicas and the shared read of untouched
+ *                   workers' rows save is still in it.
+ * After sparse steps the averaged rows and the rows read are counted on the device: the call then synchronises the
+ * stream. */
 int laa_bytes_moved(laa_handle h, uint64_t *moved_bytes, uint64_t *literal_bytes);
 
 /* Optional allocation helper for the state arrays (the library never needs it: any device memory

@@ -46,7 +46,8 @@ struct laa_ctx {
     float *partials = nullptr;        // partial sums of rows listed many times
     int64_t partial_cap = 0;          // floats allocated
     uint32_t *dirty_count = nullptr, *scan_scratch = nullptr;
-    unsigned long long *bad = nullptr;    // [0] out-of-range indices skipped, [1] rows averaged by sparse syncs
+    unsigned long long *touched = nullptr;    // per table row: the workers that stepped it since the last sync (W <= 64)
+    unsigned long long *bad = nullptr;    // [0] out-of-range indices skipped; sparse syncs: [1] rows averaged, [2] worker rows read per matrix
     double *diag_scratch = nullptr;   // block partials + results of laa_diagnostics
     bool sparse_only_since_sync = true;   // every step since the last sync was a sparse one
     uint64_t bytes = 0;                   // bytes the launches enqueued so far read and write (collapsed state counted as such)
@@ -155,6 +156,8 @@ void free_sparse(laa_ctx *h)
     if (h->dirty_count) (void)hipFree(h->dirty_count);
     if (h->scan_scratch) (void)hipFree(h->scan_scratch);
     if (h->bad) (void)hipFree(h->bad);
+    if (h->touched) (void)hipFree(h->touched);
+    h->touched = nullptr;
     if (h->sort_keys) (void)hipFree(h->sort_keys);
     h->sort_keys = nullptr; h->sort_cap = 0;
     if (h->partials) (void)hipFree(h->partials);
@@ -178,11 +181,19 @@ int ensure_sparse(laa_ctx *h, int32_t row_len)
     hipError_t e;
     const char *what = "hipMalloc dirty bitmap";
     e = hipMalloc(&h->dirty, nw * sizeof(uint32_t));
-    if (e == hipSuccess) { what = "hipMalloc sparse counters"; e = hipMalloc(&h->bad, 2 * sizeof(unsigned long long)); }
+    if (e == hipSuccess) { what = "hipMalloc sparse counters"; e = hipMalloc(&h->bad, 3 * sizeof(unsigned long long)); }
+    if (e == hipSuccess && h->W <= 64) {  // one bit per worker in a 64-bit word per row; more workers: not recorded
+        what = "hipMalloc touched-worker words";
+        e = hipMalloc(&h->touched, (size_t)n_rows * sizeof(unsigned long long));
+    }
     if (e == hipSuccess) { what = "clear dirty bitmap"; e = laa::launch_fill_u32(h->dirty, 0u, nw, h->stream); }
+    if (e == hipSuccess && h->touched) {
+        what = "clear touched-worker words";
+        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->touched), 0u, 2 * n_rows, h->stream);
+    }
     if (e == hipSuccess) {
         what = "clear sparse counters";
-        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 4, h->stream);
+        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad), 0u, 6, h->stream);
     }
     if (e != hipSuccess) {
         free_sparse(h);                   // all or nothing: the next call starts from scratch
@@ -229,6 +240,8 @@ int clear_dirty(laa_ctx *h)
 {
     if (!h->dirty) return LAA_OK;
     hipError_t e = laa::launch_fill_u32(h->dirty, 0u, n_dirty_words(h->n_rows), h->stream);
+    if (e == hipSuccess && h->touched)
+        e = laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->touched), 0u, 2 * h->n_rows, h->stream);
     return e == hipSuccess ? LAA_OK : hip_fail(e, "clear dirty bitmap");
 }
 
@@ -454,7 +467,7 @@ int laa_init_state(laa_handle h, const float *x0)
     hipError_t e = laa::launch_init(h->x, h->acc, h->snap, x0, b0sq, h->d, h->pitch, h->W, h->stream);
     if (e != hipSuccess) return hip_fail(e, "init kernel launch");
     h->t = 0; h->s = 0; h->bytes = 0; h->bytes_literal = 0; h->sparse_only_since_sync = true; h->collapsed = false;
-    if (h->bad && laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad + 1), 0u, 2, h->stream) != hipSuccess)
+    if (h->bad && laa::launch_fill_u32(reinterpret_cast<uint32_t *>(h->bad + 1), 0u, 4, h->stream) != hipSuccess)
         return fail(LAA_EHIP, "clearing the sparse-sync row counter");
     return clear_dirty(h);
 }
@@ -642,7 +655,7 @@ int laa_local_step_sparse(laa_handle h, const int32_t *idx, const float *vals, i
     if ((rc = materialize(h)) != LAA_OK) return rc;      // the row kernel reads every worker's own rows
     laa::SparseArgs a{};
     a.x = h->x; a.acc = h->acc; a.snap = h->snap;
-    a.idx = idx; a.vals = vals; a.dirty = h->dirty; a.bad = h->bad;
+    a.idx = idx; a.vals = vals; a.dirty = h->dirty; a.touched = h->touched; a.bad = h->bad;
     a.d = h->d; a.pitch = h->pitch; a.n_rows = h->n_rows; a.W = h->W; a.k = k; a.row_len = row_len;
     a.eta = eta_at(h, h->t + 1);
     a.pad = (float)(h->s + 1) * (float)(h->eps * h->eps);
@@ -716,8 +729,8 @@ static int sync_impl(laa_handle h, bool use_static)
         // their scan, the count, the first `count` list entries): nothing has to start at zero
         e = laa::launch_compact_dirty(h->dirty, h->n_rows, list, count, scan, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row compaction launch");
-        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, list, count, h->bad + 1,
-                                  h->stream);
+        e = laa::launch_mean_rows(h->x, h->acc, h->snap, h->pitch, h->W, h->wt, h->row_len, list, count, h->touched,
+                                  h->bad + 1, h->stream);
         if (e != hipSuccess) return hip_fail(e, "dirty-row mean launch");
     } else {
         const bool collapse = h->lazy && !x_only;
@@ -832,16 +845,19 @@ int laa_diagnostics(laa_handle h, double *out)
 int laa_bytes_moved(laa_handle h, uint64_t *moved_bytes, uint64_t *literal_bytes)
 {
     if (!h || (!moved_bytes && !literal_bytes)) return fail(LAA_EINVAL, "null argument");
-    uint64_t sparse_sync = 0;
-    if (h->bad) {                       // rows averaged by sparse syncs are counted on the device
-        unsigned long long rows = 0;
-        hipError_t e = hipMemcpyAsync(&rows, h->bad + 1, sizeof(rows), hipMemcpyDeviceToHost, h->stream);
+    uint64_t sparse_sync = 0, sparse_sync_literal = 0;
+    if (h->bad) {                       // what the sparse syncs averaged and read is counted on the device
+        unsigned long long c[2] = {0, 0};   // rows averaged; worker rows read per matrix
+        hipError_t e = hipMemcpyAsync(c, h->bad + 1, sizeof(c), hipMemcpyDeviceToHost, h->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
-        if (e != hipSuccess) return hip_fail(e, "reading the sparse-sync row counter");
-        sparse_sync = (uint64_t)rows * (uint64_t)(16 * h->W + 4) * (uint64_t)h->row_len;
+        if (e != hipSuccess) return hip_fail(e, "reading the sparse-sync counters");
+        // per listed row: the touched workers' rows of x and acc and one untouched worker's are read, every worker's
+        // rows and snap's are written; literally, every worker's rows are read
+        sparse_sync = (2 * (uint64_t)c[1] + (uint64_t)c[0] * (uint64_t)(2 * h->W + 1)) * 4 * (uint64_t)h->row_len;
+        sparse_sync_literal = (uint64_t)c[0] * (uint64_t)(16 * h->W + 4) * (uint64_t)h->row_len;
     }
     if (moved_bytes) *moved_bytes = h->bytes + sparse_sync;
-    if (literal_bytes) *literal_bytes = h->bytes_literal + sparse_sync;
+    if (literal_bytes) *literal_bytes = h->bytes_literal + sparse_sync_literal;
     return LAA_OK;
 }
 

@@ -60,6 +60,7 @@ struct SparseArgs {
     const uint64_t *keys; // [W][k] sorted (row << 32 | position in the list), coalescing step only
     float *partials;     // coalesce_partial_rows(W, k) rows of row_len floats, coalescing step only
     uint32_t *dirty;     // bitmap, one bit per row
+    unsigned long long *touched; // one word per row: bit w set once worker w has stepped the row (null: not recorded)
     unsigned long long *bad; // count of skipped out-of-range indices
     int64_t d;
     int64_t pitch;
@@ -80,9 +81,12 @@ hipError_t launch_sparse_step_coalesce(const SparseArgs &a, hipStream_t s);
 int64_t compact_scratch_words(int64_t n_rows);
 hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *list, uint32_t *count,
                                 uint32_t *scratch, hipStream_t s);
-// rows_total (may be null): the number of rows averaged is added to it, for byte accounting
+// touched (may be null, must be null when W > 64): per row, the workers that stepped it since the last averaging; the
+// others' rows still hold the last averaged state, so one of them is read in place of all of them.
+// totals (may be null), for byte accounting: totals[0] += rows averaged, totals[1] += worker rows read per matrix.
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,
-                            const int32_t *list, const uint32_t *count, unsigned long long *rows_total, hipStream_t s);
+                            const int32_t *list, const uint32_t *count, const unsigned long long *touched,
+                            unsigned long long *totals, hipStream_t s);
 int32_t diag_scratch_doubles();
 hipError_t launch_diagnostics(const StepArgs &a, double *scratch, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);

@@ -60,6 +60,13 @@ static constexpr int WAVE = 64;
 static constexpr int WAVES_PER_BLOCK = BLOCK / WAVE;
 // (64-thread blocks: the same 0.129 ms on the embedding workload; non-temporal accesses to x and acc: 0.137-0.147 ms,
 // the frequent rows are served from the caches.)
+// Row r has been stepped by worker w: its bit in the bitmap, and the worker's bit in the row's word.
+__device__ __forceinline__ void mark_row(const SparseArgs &a, int32_t r, int32_t w)
+{
+    atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+    if (a.touched) atomicOr(&a.touched[r], 1ull << w);
+}
+
 __global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
 {
     const int64_t pair = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x / WAVE);
@@ -89,7 +96,7 @@ __global__ __launch_bounds__(BLOCK) void sparse_step_kernel(const SparseArgs a)
         st<4, false>(xr + e, xv);
         st<4, false>(br + e, bv);
     }
-    if (lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+    if (lane == 0) mark_row(a, r, w);
 }
 
 // Row-sparse step for lists in which one worker may name a row several times (a batch of tokens with repeated
@@ -213,7 +220,7 @@ __global__ __launch_bounds__(BLOCK) void sparse_step_coalesce_kernel(const Spars
             if (whole) sparse_row_update(a, xr, br, sr, e, g);
             else st<4, false>(dst + e, g);
         }
-        if (whole && lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+        if (whole && lane == 0) mark_row(a, r, w);
     } else {
         if (!head || !goes_on) return;
         int32_t m = 0;                                               // pieces after the first: at bnd, bnd + SEG, ...
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(BLOCK) void sparse_step_coalesce_kernel(const Spars
             }
             sparse_row_update(a, xr, br, sr, e, g);
         }
-        if (lane == 0) atomicOr(&a.dirty[r >> 5], 1u << (r & 31));
+        if (lane == 0) mark_row(a, r, w);
     }
 }
 
@@ -321,9 +328,10 @@ __global__ __launch_bounds__(BLOCK) void dirty_write_kernel(const uint32_t *__re
 
 // Synchronize branch restricted to the listed rows.  The length of the list is only known on the device, so a fixed
 // grid of one-wavefront blocks strides over the work items, an item being 256 consecutive floats of a listed row
-// (16 bytes per lane) for all W workers: 2W non-temporal 16-byte loads in flight per lane, 2W + 1 stores.  The row
+// (16 bytes per lane) for all W workers: up to 2W non-temporal 16-byte loads in flight per lane, 2W + 1 stores.  The row
 // number of the next item is fetched before the current item's loads are waited for.  Measured on the embedding
-// workload (290 000 of 800 000 rows of 512 floats listed, W = 8; list compaction included): 3.14 ms with 2 wavefronts
+// workload (290 000 of 800 000 rows of 512 floats listed, W = 8; list compaction included) while every worker's
+// row was read (with the shared read of untouched workers' rows below: 2.12 ms): 3.14 ms with 2 wavefronts
 // per SIMD (8 blocks per CU), 3.18 with 3, 3.23 with 4, 3.17-3.21 uncapped with 32 blocks per CU; 3.35 with cached
 // instead of non-temporal accesses, 3.33 with one block per item under a grid that covers the largest possible list
 // (most of its blocks leave at once).
@@ -339,38 +347,71 @@ static constexpr bool ROWS_NT = LAA_ROWS_NT;
 #ifndef LAA_ROWS_WAVES
 #define LAA_ROWS_WAVES 2               // wavefronts per SIMD; the grid holds exactly that many per CU
 #endif
+// The workers that did not step a row since the last averaging all still hold that averaging's result in it, bit
+// for bit; `touched` names the ones that did.  One untouched worker's row is read in place of every untouched
+// worker's: the same values enter the same sum, so the mean is the one the full read gives.  (A row touched by a
+// single worker costs 2 + 2 row reads instead of 2W; on the embedding workload a touched row has 1.97 touching
+// workers on average.)
+__device__ __forceinline__ uint64_t touched_workers(const unsigned long long *touched, int32_t row, int32_t W)
+{
+    const uint64_t all = W >= 64 ? ~0ull : (1ull << W) - 1;
+    if (!touched) return all;
+    const uint64_t m = touched[row];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)m), hi = __builtin_amdgcn_readfirstlane((uint32_t)(m >> 32));
+    const uint64_t u = (((uint64_t)hi << 32) | lo) & all;
+    return u ? u : all;                    // a listed row with no worker recorded: read them all
+}
+
 template <int WT>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(1, LAA_ROWS_WAVES))) void mean_rows_kernel(float *__restrict__ x, float *__restrict__ acc,
                                                          float *__restrict__ snap, int64_t pitch, int32_t W,
                                                          int32_t row_len, const int32_t *__restrict__ list,
                                                          const uint32_t *__restrict__ count,
-                                                         unsigned long long *__restrict__ rows_total)
+                                                         const unsigned long long *__restrict__ touched,
+                                                         unsigned long long *__restrict__ totals)
 {
     const uint32_t n = *count;
-    if (rows_total && blockIdx.x == 0 && threadIdx.x == 0) *rows_total += n;
+    if (totals && blockIdx.x == 0 && threadIdx.x == 0) totals[0] += n;
     const uint32_t chunks = (uint32_t)(row_len + WAVE * 4 - 1) / (WAVE * 4);
     const uint64_t items = (uint64_t)n * chunks;
     uint64_t it = blockIdx.x;
     if (it >= items) return;
     const int lane = threadIdx.x;
     const MeanOf mean(W);
+    const uint64_t all = W >= 64 ? ~0ull : (1ull << W) - 1;
+    unsigned long long rows_read = 0;
     int32_t row = list[it / chunks];
+    uint64_t m = touched_workers(touched, row, W);
     while (true) {
         const uint64_t nxt = it + gridDim.x;
         const bool more = nxt < items;
         const int32_t row_next = more ? list[nxt / chunks] : 0;
-        const int32_t e = (int32_t)(it % chunks) * (WAVE * 4) + lane * 4;
+        const uint64_t m_next = more ? touched_workers(touched, row_next, W) : all;
+        const int32_t chunk = (int32_t)(it % chunks);
+        const int32_t e = chunk * (WAVE * 4) + lane * 4;
+        const bool some_untouched = m != all;
+        if (chunk == 0) rows_read += (unsigned long long)__builtin_popcountll(m) + (some_untouched ? 1 : 0);
         if (e < row_len) {
             const int64_t col = (int64_t)row * row_len + e;
-            Pack<4> sx, sb;
+            Pack<4> sx, sb, xu, bu;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) sx.v[c] = sb.v[c] = 0.0f;
+            for (int c = 0; c < 4; ++c) sx.v[c] = sb.v[c] = xu.v[c] = bu.v[c] = 0.0f;
+            if (some_untouched) {
+                const int32_t u = __builtin_ctzll(~m & all);
+                xu = ld<4, ROWS_NT>(x + (int64_t)u * pitch + col);
+                bu = ld<4, ROWS_NT>(acc + (int64_t)u * pitch + col);
+            }
             for (int32_t w0 = 0; w0 < W; w0 += WT) {
                 Pack<4> xv[WT], bv[WT];
 #pragma unroll
                 for (int k = 0; k < WT; ++k) {
-                    xv[k] = ld<4, ROWS_NT>(x + (int64_t)(w0 + k) * pitch + col);
-                    bv[k] = ld<4, ROWS_NT>(acc + (int64_t)(w0 + k) * pitch + col);
+                    if (!some_untouched || ((m >> ((w0 + k) & 63)) & 1)) {
+                        xv[k] = ld<4, ROWS_NT>(x + (int64_t)(w0 + k) * pitch + col);
+                        bv[k] = ld<4, ROWS_NT>(acc + (int64_t)(w0 + k) * pitch + col);
+                    } else {
+                        xv[k] = xu;
+                        bv[k] = bu;
+                    }
                 }
                 const Pack<4> tx = tree_sum<4, WT>(xv), tb = tree_sum<4, WT>(bv);
 #pragma unroll
@@ -387,7 +428,9 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(1, LAA_ROW
         if (!more) break;
         it = nxt;
         row = row_next;
+        m = m_next;
     }
+    if (totals && lane == 0 && rows_read) atomicAdd(totals + 1, rows_read);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -693,12 +736,13 @@ hipError_t launch_compact_dirty(const uint32_t *dirty, int64_t n_rows, int32_t *
 }
 
 hipError_t launch_mean_rows(float *x, float *acc, float *snap, int64_t pitch, int32_t W, int32_t wt, int32_t row_len,
-                            const int32_t *list, const uint32_t *count, unsigned long long *rows_total, hipStream_t s)
+                            const int32_t *list, const uint32_t *count, const unsigned long long *touched,
+                            unsigned long long *totals, hipStream_t s)
 {
     if (W <= 0 || wt <= 0 || W % wt != 0 || row_len <= 0 || row_len % 4 != 0) return hipErrorInvalidValue;
-    if (!x || !acc || !snap || !list || !count) return hipErrorInvalidValue;
+    if (!x || !acc || !snap || !list || !count || (touched && W > 64)) return hipErrorInvalidValue;
     const dim3 grid(N_CU * LAA_ROWS_WAVES_PER_CU), block(WAVE);
-#define LAA_ROWS(WT) hipLaunchKernelGGL((mean_rows_kernel<WT>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count, rows_total)
+#define LAA_ROWS(WT) hipLaunchKernelGGL((mean_rows_kernel<WT>), grid, block, 0, s, x, acc, snap, pitch, W, row_len, list, count, touched, totals)
     switch (wt) {               // the same batches as the dense mean: one order of the worker-axis sum everywhere
     case 8: LAA_ROWS(8); break;
     case 4: LAA_ROWS(4); break;
