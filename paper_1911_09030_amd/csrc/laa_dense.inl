@@ -65,9 +65,10 @@ template <int VEC, bool NT> __device__ __forceinline__ void st(float *p, const P
     }
 }
 
-// The same with the address split into a part that is uniform over the wavefront (kernel arguments, block index:
-// held in scalar registers) and a small per-lane element offset: the load/store then takes the scalar base and a
-// 32-bit vector offset, and no per-lane 64-bit address arithmetic is needed.
+// The same with the address split into a part that is uniform over the wavefront (kernel arguments, block index,
+// worker row: computed once on the scalar unit) and a small per-lane element offset.  The compiler then uses the
+// scalar-base addressing form or, for the non-temporal accesses, forms the address with a single 64-bit add of the
+// scalar base and the lane offset, instead of per-lane 64-bit multiply-adds for every stream.
 template <int VEC, bool NT> __device__ __forceinline__ Pack<VEC> ld(const float *base, uint32_t lane_off)
 {
     return ld<VEC, NT>(base + lane_off);
