@@ -112,7 +112,9 @@ int laa_materialize(laa_handle h);
 /* Hand over the state arrays (device, caller-owned, must outlive the handle's
  * use): x [W][d], acc [W][d] (running B2 of each worker), snap [d] (B2 at the
  * last sync), and the HIP stream (hipStream_t, may be null for the default
- * stream) on which all work is enqueued. */
+ * stream) on which all work is enqueued.  Attaching other arrays in the middle
+ * of a period is allowed; the next sync then averages the whole table even if
+ * only sparse steps were taken (as after laa_set_counters). */
 int laa_attach(laa_handle h, float *x, float *acc, float *snap, void *hip_stream);
 
 /* The same with rows `pitch` >= d elements apart: x, acc (and every other [W][.] array handed to

@@ -261,6 +261,18 @@ class LocalAdaAlter:
                                          _dev_ptr(self.snap, torch.float32), self.pitch,
                                          C.c_void_p(self.stream.cuda_stream)))
 
+    def attach(self, x, acc, snap):
+        """Hand other state arrays (same shapes, same row pitch) to the handle."""
+        for t, shape in ((x, (self.W, self.d)), (acc, (self.W, self.d)), (snap, (self.d,))):
+            if tuple(t.shape) != shape:
+                raise ValueError(f"expected an array of shape {shape}, got {tuple(t.shape)}")
+        if x.stride(0) != self.pitch or acc.stride(0) != self.pitch:
+            raise ValueError(f"rows must be {self.pitch} elements apart")
+        self.x, self.acc, self.snap = x, acc, snap
+        _check(self.L.laa_attach_pitched(self.h, self._rows_ptr(self.x), self._rows_ptr(self.acc),
+                                         _dev_ptr(self.snap, self.torch.float32), self.pitch,
+                                         C.c_void_p(self.stream.cuda_stream)))
+
     def rows(self, src=None):
         """A [W][d] device array whose rows are ``pitch`` apart (a view of a [W][pitch] buffer), optionally
         filled from ``src`` (a [W][d] tensor)."""

@@ -454,6 +454,8 @@ int laa_attach_pitched(laa_handle h, float *x, float *acc, float *snap, int64_t 
     h->pitch = pitch;
     h->vec4 = h->d % 4 == 0 && pitch % 4 == 0 && aligned(x, 16) && aligned(acc, 16) && aligned(snap, 16);
     h->attached = true;
+    if (h->s > 0) h->sparse_only_since_sync = false;   // other arrays in the middle of a period: which of their rows
+                                                       // differ between workers is unknown, the next sync takes them all
     config_changed(h);
     return LAA_OK;
 }

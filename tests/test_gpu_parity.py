@@ -760,6 +760,30 @@ def test_sparse_edge_cases(B):
     parity.assert_state(host(g.x), host(g.acc), host(g.snap), o, parity.FULL_RUN, what="mixed period", scale=sc)
 
 
+def test_other_arrays_attached_mid_period_are_averaged_whole(B):
+    """Arrays handed over in the middle of a period may differ between workers anywhere, not only in the rows the
+    handle saw being stepped: the next averaging takes the whole table."""
+    import torch
+    W, rows, row_len, H = 4, 50, 8, 3
+    d = rows * row_len
+    g = B.LocalAdaAlter(d, W, H, 0.5, 1.0); g.init_state()
+    idx = np.array([[1], [1], [7], [9]], dtype=np.int32)
+    g.local_step_sparse(dev(idx), dev(np.ones((W, 1, row_len), dtype=np.float32)), row_len)
+    x2, acc2, snap2 = g.x.clone(), g.acc.clone(), g.snap.clone()
+    x2[2, 30 * row_len] = 4.0                        # a row that no sparse step listed
+    g.attach(x2, acc2, snap2)
+    assert g.counters() == (1, 1)
+    g.sync()
+    torch.cuda.synchronize()
+    assert torch.all(g.x[:, 30 * row_len] == 1.0)    # (0 + 0 + 4 + 0) / 4 on every worker
+    assert np.array_equal(g.dirty_rows(), np.zeros(0, dtype=np.int32))
+    # at a period boundary the handle keeps relying on the listed rows
+    g.local_step_sparse(dev(idx), dev(np.ones((W, 1, row_len), dtype=np.float32)), row_len)
+    g.sync()
+    torch.cuda.synchronize()
+    assert all(torch.equal(g.x[0], g.x[w]) and torch.equal(g.acc[w], g.snap) for w in range(W))
+
+
 @pytest.mark.parametrize("W,tile,row_len", [(8, 8, 16), (8, 4, 16), (8, 2, 16), (4, 1, 16), (2, 2, 16), (8, 8, 520),
                                              (64, 8, 8), (16, 4, 260), (3, 1, 16), (6, 2, 520), (1, 1, 16)])
 def test_sparse_sync_equals_dense_sync_bit_for_bit(B, W, tile, row_len):
