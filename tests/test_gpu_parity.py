@@ -916,7 +916,7 @@ def test_sparse_coalesce_bad_rows_and_limit(B):
                           torch.zeros((1, 8193, 4), device="cuda:0"), 4)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(20))
 def test_random_call_sequences_follow_the_oracle(B, seed):
     """Seeded random sequences over the whole boundary (explicit, generated and row-sparse steps, local and fused;
     early, due and empty syncs; lazy replicas and row coalescing switched on and off; materialize; resume; whole
