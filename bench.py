@@ -92,6 +92,20 @@ def traffic_from_profile(kernel_tag: str):
     return None, None
 
 
+def valu_from_profile(kernel_tag: str):
+    """Vector-ALU utilisation (per cent) and vector instructions per element-update of the dominant kernel as last
+    profiled (rocprofv3 SQ counters) and the committed file they are read from; (None, None, None) if there is none."""
+    import re
+    rel = os.path.join("profiles", f"valu_{kernel_tag}.txt")
+    try:
+        text = open(os.path.join(ROOT, rel)).read()
+    except OSError:
+        return None, None, None
+    busy = re.search(r"VALUBusy ([0-9.]+) %", text)           # the first block of the file is the plain step
+    per = re.search(r"= ([0-9.]+) per element-update", text)
+    return (float(busy.group(1)) if busy else None), (float(per.group(1)) if per else None), rel
+
+
 def _oracle_period(c, lo, n, offsets):
     """One sync period of the fp64 oracle on the columns [lo, lo + n) of workload c; returns the seconds it took."""
     import numpy as np
@@ -551,6 +565,7 @@ def main():
         del gp, pa, pxs
 
     traffic, traffic_source = traffic_from_profile(kernel_tag)
+    valu_busy, valu_per_update, valu_source = valu_from_profile(kernel_tag)
     frac = achieved / HBM_PEAK_GBS
     out = {
         "metric": "element-updates/sec and achieved HBM GB/s (% of peak), step+sync, 1 GPU",
@@ -575,6 +590,8 @@ def main():
                      "frac": frac, "target_frac": 0.80, "meets_target": frac >= 0.80,
                      "traffic": traffic, "traffic_source": (f"stored: {traffic_source} (rocprofv3 counters of an earlier run "
                                                             "of this command, not measured in this run)") if traffic_source else None,
+                     "valu_busy_pct": valu_busy, "valu_instructions_per_element_update": valu_per_update,
+                     "valu_source": f"stored: {valu_source} (rocprofv3 counters of an earlier run)" if valu_source else None,
                      "kernel": kernel_name, "kernel_ms": kern_ms, "kernel_ms_min": min(plain),
                      "kernel_ms_median": statistics.median(plain), "kernel_ms_max": max(plain), "kernel_launches_timed": len(plain),
                      "algorithmic_bytes_per_launch": step_bytes, "copy_kernel_gbs_same_run": copy_gbs},
