@@ -22,7 +22,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def _period(B, W, rows, row_len, k, H, seed, stale_first=False):
+def _period(B, W, rows, row_len, k, H, seed):
     """Two handles take the same sparse steps; one averages with laa_sync, the other with laa_sync_static."""
     import torch
     print(f"sync_static W={W} rows={rows} row_len={row_len} k={k} H={H}", flush=True)
