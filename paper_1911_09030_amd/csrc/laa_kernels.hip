@@ -390,7 +390,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(1, LAA_ROW
         const int32_t chunk = (int32_t)(it % chunks);
         const int32_t e = chunk * (WAVE * 4) + lane * 4;
         const bool some_untouched = m != all;
-        if (chunk == 0) rows_read += (unsigned long long)__builtin_popcountll(m) + (some_untouched ? 1 : 0);
+        if (chunk == 0) rows_read += some_untouched ? (unsigned long long)__builtin_popcountll(m) + 1 : (unsigned long long)W;
         if (e < row_len) {
             const int64_t col = (int64_t)row * row_len + e;
             Pack<4> sx, sb, xu, bu;

@@ -816,6 +816,9 @@ def test_sparse_sync_equals_dense_sync_bit_for_bit(B, W, tile, row_len):
             # carry on from one common state: the rows not listed differ in the last bit after a whole-table mean
             sp.x.copy_(de.x); sp.acc.copy_(de.acc); sp.snap.copy_(de.snap)
         assert listed.size > 0 and (W == 1 or W > 64 or listed.size < rows)       # 80 workers list every row
+    if W > 64:        # no per-row record of the workers: every worker's rows are read, and counted as such
+        moved, literal = sp.bytes_moved(literal=True)
+        assert moved == literal
 
 
 def _zipf_with_repeats(rows, W, k, rng, s=1.1):
